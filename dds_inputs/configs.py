@@ -1,0 +1,228 @@
+"""Network descriptions for the five benchmark configurations (pure data).
+
+An op record is a dict with key "op" in
+  conv      : cin, cout, k, stride, pad      (2-D convolution + bias)
+  linear    : cin, cout                      (dense layer + bias, on [N, cin, 1, 1])
+  relu
+  maxpool2                                   (2x2 window, stride 2)
+  gap                                        (global average pool -> [N, C, 1, 1])
+  res_begin                                  (remember the current tensor as block input)
+  res_add   : scale, shortcut                (y = shortcut(x_in) + scale * y_main;
+                                              shortcut is None (identity) or a dict
+                                              cin, cout, k, stride, pad of a conv + bias)
+  softmax_ce                                 (mean softmax cross-entropy, last op)
+
+`bounds` has K+1 indices into the op list: module k0 owns ops[bounds[k0]:bounds[k0+1]].
+The residual networks are BatchNorm-free: every block output is
+relu(shortcut(x) + scale * (conv2(relu(conv1(x))))), scale = 1/sqrt(number of blocks).
+"""
+from __future__ import annotations
+
+import copy
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+
+@dataclass
+class Workload:
+    name: str
+    ops: List[dict]
+    bounds: List[int]
+    K: int
+    W: int
+    B: int
+    in_shape: tuple  # (C, H, W) of one sample as the caller lays it out (NCHW)
+    classes: int
+    precision: str  # "f32" | "bf16"  (bf16 = bf16 activations/weights + fp32 master)
+    lr: float
+    momentum: float
+    steps: int
+    delays: Optional[List[int]] = None  # None -> the paper's schedule d_k = K-1-k0
+    notes: str = ""
+    extra: dict = field(default_factory=dict)
+
+
+def _conv(cin, cout, k=3, stride=1, pad=None):
+    if pad is None:
+        pad = (k - 1) // 2
+    return {"op": "conv", "cin": cin, "cout": cout, "k": k, "stride": stride, "pad": pad}
+
+
+def _linear(cin, cout):
+    return {"op": "linear", "cin": cin, "cout": cout}
+
+
+def _relu():
+    return {"op": "relu"}
+
+
+def _block(cin, cout, stride, scale):
+    sc = None
+    if stride != 1 or cin != cout:
+        sc = {"cin": cin, "cout": cout, "k": 1, "stride": stride, "pad": 0}
+    return [
+        {"op": "res_begin"},
+        _conv(cin, cout, 3, stride),
+        _relu(),
+        _conv(cout, cout, 3, 1),
+        {"op": "res_add", "scale": scale, "shortcut": sc},
+        _relu(),
+    ]
+
+
+def _mlp():
+    ops = [
+        _linear(3072, 256), _relu(),
+        _linear(256, 256), _relu(),
+        _linear(256, 10), {"op": "softmax_ce"},
+    ]
+    return Workload(
+        name="cfg0_mlp", ops=ops, bounds=[0, 2, 4, 6], K=3, W=2, B=32,
+        in_shape=(3072, 1, 1), classes=10, precision="f32", lr=0.01, momentum=0.0, steps=20,
+        notes="32x32x3 image flattened in NCHW order to 3072 features",
+    )
+
+
+def _cnn():
+    ops, bounds = [], [0]
+    cin = 3
+    for j, cout in enumerate((64, 128, 256, 512)):
+        ops += [_conv(cin, cout), _relu(), {"op": "maxpool2"}]
+        cin = cout
+        if j < 3:
+            bounds.append(len(ops))
+    ops += [{"op": "gap"}, _linear(512, 10), {"op": "softmax_ce"}]
+    bounds.append(len(ops))
+    return Workload(
+        name="cfg1_cnn", ops=ops, bounds=bounds, K=4, W=4, B=128, in_shape=(3, 32, 32),
+        classes=10, precision="f32", lr=0.01, momentum=0.9, steps=100,
+    )
+
+
+def _resnet(name, stem, stages, module_blocks, K, W, B, steps):
+    """stages: list of (channels, n_blocks); module_blocks: blocks per module (len K)."""
+    nblocks = sum(n for _, n in stages)
+    assert sum(module_blocks) == nblocks and len(module_blocks) == K
+    scale = 1.0 / math.sqrt(nblocks)
+    blocks = []
+    cin = stem
+    for si, (c, n) in enumerate(stages):
+        for bi in range(n):
+            stride = 2 if (bi == 0 and si > 0) else 1
+            blocks.append(_block(cin, c, stride, scale))
+            cin = c
+    ops = [_conv(3, stem), _relu()]
+    bounds = [0]
+    it = iter(blocks)
+    for k0, nb in enumerate(module_blocks):
+        for _ in range(nb):
+            ops += next(it)
+        if k0 < K - 1:
+            bounds.append(len(ops))
+    ops += [{"op": "gap"}, _linear(cin, 10), {"op": "softmax_ce"}]
+    bounds.append(len(ops))
+    return Workload(
+        name=name, ops=ops, bounds=bounds, K=K, W=W, B=B, in_shape=(3, 32, 32), classes=10,
+        precision="bf16", lr=0.01, momentum=0.0, steps=steps,
+        extra={"blocks": nblocks, "res_scale": scale},
+    )
+
+
+def _resnet18():
+    return _resnet("cfg2_resnet18", 64, [(64, 2), (128, 2), (256, 2), (512, 2)],
+                   [2, 2, 2, 2], K=4, W=4, B=128, steps=16)
+
+
+def _resnet56():
+    cuts = [int(round(i * 27 / 8)) for i in range(9)]
+    per_module = [cuts[i + 1] - cuts[i] for i in range(8)]
+    return _resnet("cfg3_resnet56", 16, [(16, 9), (32, 9), (64, 9)], per_module,
+                   K=8, W=8, B=128, steps=24)
+
+
+def _resnet34w():
+    return _resnet("cfg4_resnet34w", 128, [(128, 3), (256, 4), (512, 6), (1024, 3)],
+                   [2] * 8, K=8, W=8, B=256, steps=24)
+
+
+_BUILDERS = {
+    "cfg0_mlp": _mlp,
+    "cfg1_cnn": _cnn,
+    "cfg2_resnet18": _resnet18,
+    "cfg3_resnet56": _resnet56,
+    "cfg4_resnet34w": _resnet34w,
+}
+WORKLOAD_NAMES = tuple(_BUILDERS)
+
+
+def workload(name: str, *, B: Optional[int] = None, W: Optional[int] = None,
+             steps: Optional[int] = None, precision: Optional[str] = None,
+             lr: Optional[float] = None, momentum: Optional[float] = None) -> Workload:
+    """Return a fresh copy of a named configuration, optionally with a reduced
+    per-replica batch / replica count / step count (used by parity tests whose
+    oracle leg must finish in seconds)."""
+    wl = copy.deepcopy(_BUILDERS[name]())
+    if B is not None:
+        wl.B = B
+    if W is not None:
+        wl.W = W
+    if steps is not None:
+        wl.steps = steps
+    if precision is not None:
+        wl.precision = precision
+    if lr is not None:
+        wl.lr = lr
+    if momentum is not None:
+        wl.momentum = momentum
+    return wl
+
+
+def tiny_resnet(K=2, W=2, B=4, hw=8, c=8, precision="f32", steps=8) -> Workload:
+    """A 3-block residual net on hw x hw images (one projection block), small
+    enough for finite differences and exhaustive checks."""
+    scale = 1.0 / math.sqrt(3)
+    ops = [_conv(3, c), _relu()]
+    ops += _block(c, c, 1, scale)
+    cut = len(ops)
+    ops += _block(c, 2 * c, 2, scale)
+    ops += _block(2 * c, 2 * c, 1, scale)
+    ops += [{"op": "gap"}, _linear(2 * c, 10), {"op": "softmax_ce"}]
+    if K == 1:
+        bounds = [0, len(ops)]
+    elif K == 2:
+        bounds = [0, cut, len(ops)]
+    elif K == 3:
+        bounds = [0, cut, cut + 6, len(ops)]
+    else:
+        raise ValueError("tiny_resnet supports K in 1..3")
+    return Workload(name=f"tiny_resnet_K{K}", ops=ops, bounds=bounds, K=K, W=W, B=B,
+                    in_shape=(3, hw, hw), classes=10, precision=precision, lr=0.05,
+                    momentum=0.0, steps=steps, extra={"blocks": 3, "res_scale": scale})
+
+
+def tiny_cnn(K=2, W=2, B=4, hw=8, c=4, precision="f32", steps=8, momentum=0.9) -> Workload:
+    """conv-relu-maxpool x2, gap, linear: the cfg1 structure at toy size."""
+    ops = [_conv(3, c), _relu(), {"op": "maxpool2"}]
+    cut = len(ops)
+    ops += [_conv(c, 2 * c), _relu(), {"op": "maxpool2"}, {"op": "gap"}, _linear(2 * c, 10),
+            {"op": "softmax_ce"}]
+    bounds = [0, len(ops)] if K == 1 else [0, cut, len(ops)]
+    return Workload(name=f"tiny_cnn_K{K}", ops=ops, bounds=bounds, K=K, W=W, B=B,
+                    in_shape=(3, hw, hw), classes=10, precision=precision, lr=0.05,
+                    momentum=momentum, steps=steps)
+
+
+def tiny_mlp(K=3, W=2, B=4, feat=12, hidden=8, precision="f32", steps=10) -> Workload:
+    """K linear layers (ReLU between), one per module: the cfg0 structure at toy size."""
+    ops, bounds = [], [0]
+    cin = feat
+    for k0 in range(K):
+        last = k0 == K - 1
+        ops.append(_linear(cin, 10 if last else hidden))
+        ops.append({"op": "softmax_ce"} if last else _relu())
+        cin = hidden
+        bounds.append(len(ops))
+    return Workload(name=f"tiny_mlp_K{K}", ops=ops, bounds=bounds, K=K, W=W, B=B,
+                    in_shape=(feat, 1, 1), classes=10, precision=precision, lr=0.05,
+                    momentum=0.0, steps=steps)

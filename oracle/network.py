@@ -1,0 +1,117 @@
+"""Forward and backward pass of a contiguous group of layers g(k) = {p_k..q_k}
+(Section 3.2), op by op, fp64.
+
+`ops` is a list of op records (dicts with key "op": conv, linear, relu, maxpool2,
+gap, res_begin, res_add, softmax_ce); `params` is the flat list of that group's
+weight tensors in canonical order (for each conv/linear/projection-shortcut in op
+order: weight, then bias).
+"""
+from __future__ import annotations
+
+from typing import List
+
+import torch
+
+from . import layers as L
+
+DT = torch.float64
+
+
+def param_slots(ops) -> List[int]:
+    """Index of each op's weight tensor in the flat param list (-1 if it has none)."""
+    slots, nxt = [], 0
+    for op in ops:
+        kind = op["op"]
+        has = kind in ("conv", "linear") or (kind == "res_add" and op.get("shortcut"))
+        slots.append(nxt if has else -1)
+        if has:
+            nxt += 2
+    return slots
+
+
+def n_params(ops) -> int:
+    return sum(2 for s in param_slots(ops) if s >= 0)
+
+
+def forward(ops, params, x, labels=None):
+    """Run the ops on x. Returns (output, saved, loss). If the last op is
+    softmax_ce, output is d loss / d logits and loss is the mini-batch mean."""
+    slots = param_slots(ops)
+    saved = []
+    res_stack = []
+    h = x
+    loss = None
+    for op, ps in zip(ops, slots):
+        kind = op["op"]
+        if kind == "conv":
+            h, sv = L.conv2d_fwd(h, params[ps], params[ps + 1], op["stride"], op["pad"])
+        elif kind == "linear":
+            h, sv = L.linear_fwd(h, params[ps], params[ps + 1])
+        elif kind == "relu":
+            h, sv = L.relu_fwd(h)
+        elif kind == "maxpool2":
+            h, sv = L.maxpool2_fwd(h)
+        elif kind == "gap":
+            h, sv = L.gap_fwd(h)
+        elif kind == "res_begin":
+            res_stack.append(h)
+            sv = None
+        elif kind == "res_add":
+            xin = res_stack.pop()
+            sc = op.get("shortcut")
+            if sc:
+                short, sv = L.conv2d_fwd(xin, params[ps], params[ps + 1], sc["stride"], sc["pad"])
+            else:
+                short, sv = xin, None
+            h = short + op["scale"] * h
+        elif kind == "softmax_ce":
+            assert labels is not None
+            loss, h = L.softmax_ce_fwd(h, labels)
+            sv = None
+        else:
+            raise ValueError(kind)
+        saved.append(sv)
+    assert not res_stack
+    return h, saved, loss
+
+
+def backward(ops, params, saved, dout, need_dx=True):
+    """Chain rule through the ops in reverse. `dout` is the gradient with respect
+    to the group's output (for a group ending in softmax_ce: the d loss / d logits
+    that forward returned). Returns (dx, grads) with grads aligned to params."""
+    slots = param_slots(ops)
+    grads = [None] * len(params)
+    d = dout
+    res_grad = []  # gradients waiting to be added at the matching res_begin
+    first_weighted = next((i for i, s in enumerate(slots) if s >= 0), None)
+    for i in range(len(ops) - 1, -1, -1):
+        op, ps, sv = ops[i], slots[i], saved[i]
+        kind = op["op"]
+        # the gradient w.r.t. the group's input is needed unless this is the first
+        # weighted op of a group whose caller asked for no dx
+        want_dx = need_dx or i != first_weighted or bool(res_grad)
+        if kind == "conv":
+            d, grads[ps], grads[ps + 1] = L.conv2d_bwd(d, sv, params[ps], op["stride"], op["pad"], want_dx)
+        elif kind == "linear":
+            d, grads[ps], grads[ps + 1] = L.linear_bwd(d, sv, params[ps], want_dx)
+        elif kind == "relu":
+            d = L.relu_bwd(d, sv)
+        elif kind == "maxpool2":
+            d = L.maxpool2_bwd(d, sv)
+        elif kind == "gap":
+            d = L.gap_bwd(d, sv)
+        elif kind == "res_add":
+            sc = op.get("shortcut")
+            if sc:
+                dshort, grads[ps], grads[ps + 1] = L.conv2d_bwd(d, sv, params[ps], sc["stride"], sc["pad"], True)
+            else:
+                dshort = d
+            res_grad.append(dshort)
+            d = op["scale"] * d
+        elif kind == "res_begin":
+            d = res_grad.pop() if d is None else d + res_grad.pop()
+        elif kind == "softmax_ce":
+            pass  # dout already is d loss / d logits
+        else:
+            raise ValueError(kind)
+    return d, grads

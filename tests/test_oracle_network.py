@@ -1,0 +1,137 @@
+"""Pins for the oracle's per-module forward/backward: whole-network finite
+differences and an autograd model assembled from torch's library routines."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from dds_inputs import make_batch, make_params
+from dds_inputs.configs import tiny_cnn, tiny_mlp, tiny_resnet
+from oracle import fdg, network as N
+
+DT = torch.float64
+
+
+def _autograd_net(ops, params, x, y):
+    """Same network through torch's own conv2d/linear/max_pool2d + autograd."""
+    ps = [p.clone().requires_grad_() for p in params]
+    slots = N.param_slots(ops)
+    h, stack = x, []
+    for op, s in zip(ops, slots):
+        k = op["op"]
+        if k == "conv":
+            h = F.conv2d(h, ps[s], ps[s + 1], stride=op["stride"], padding=op["pad"])
+        elif k == "linear":
+            h = F.linear(h.flatten(1), ps[s], ps[s + 1]).view(h.shape[0], -1, 1, 1)
+        elif k == "relu":
+            h = F.relu(h)
+        elif k == "maxpool2":
+            h = F.max_pool2d(h, 2)
+        elif k == "gap":
+            h = F.adaptive_avg_pool2d(h, 1)
+        elif k == "res_begin":
+            stack.append(h)
+        elif k == "res_add":
+            xin = stack.pop()
+            sc = op["shortcut"]
+            short = F.conv2d(xin, ps[s], ps[s + 1], stride=sc["stride"], padding=sc["pad"]) if sc else xin
+            h = short + op["scale"] * h
+        elif k == "softmax_ce":
+            h = F.cross_entropy(h.flatten(1), torch.as_tensor(y, dtype=torch.int64))
+    h.backward()
+    return float(h.detach()), [p.grad for p in ps]
+
+
+def _flat_params(wl, seed=0):
+    mods = make_params(wl, seed)
+    return [torch.as_tensor(p, dtype=DT) for m in mods for p in m]
+
+
+@pytest.mark.parametrize("make", [tiny_resnet, tiny_cnn, tiny_mlp])
+def test_whole_network_gradient_matches_autograd(make):
+    wl = make()
+    params = _flat_params(wl)
+    # non-zero biases so that bias paths are exercised
+    g = torch.Generator().manual_seed(3)
+    params = [p if p.dim() > 1 else 0.1 * torch.randn(p.shape, dtype=DT, generator=g) for p in params]
+    x, y = make_batch(wl, 0, 0, 0)
+    x = torch.as_tensor(x, dtype=DT)
+    dlog, saved, loss = N.forward(wl.ops, params, x, torch.as_tensor(y, dtype=torch.int64))
+    _, grads = N.backward(wl.ops, params, saved, dlog, need_dx=False)
+    ref_loss, ref = _autograd_net(wl.ops, params, x, y)
+    assert abs(float(loss) - ref_loss) < 1e-12
+    for g1, g2 in zip(grads, ref):
+        assert torch.allclose(g1, g2, rtol=1e-10, atol=1e-12)
+
+
+def test_whole_network_gradient_matches_finite_differences():
+    wl = tiny_resnet(K=1, B=2, hw=4, c=4)
+    params = _flat_params(wl)
+    x, y = make_batch(wl, 0, 0, 0)
+    x = torch.as_tensor(x, dtype=DT)
+    yl = torch.as_tensor(y, dtype=torch.int64)
+    dlog, saved, _ = N.forward(wl.ops, params, x, yl)
+    _, grads = N.backward(wl.ops, params, saved, dlog, need_dx=False)
+    rng = np.random.default_rng(0)
+    eps = 1e-6
+    for j, p in enumerate(params):
+        flat = p.view(-1)
+        for i in rng.choice(flat.numel(), size=min(6, flat.numel()), replace=False):
+            old = float(flat[i])
+            flat[i] = old + eps
+            up = float(N.forward(wl.ops, params, x, yl)[2])
+            flat[i] = old - eps
+            dn = float(N.forward(wl.ops, params, x, yl)[2])
+            flat[i] = old
+            fd = (up - dn) / (2 * eps)
+            assert abs(fd - float(grads[j].view(-1)[i])) <= 1e-6 * max(1.0, abs(fd)), (j, i)
+
+
+def test_module_split_composes_to_the_whole_network():
+    """Running the K groups one after another (forward) and in reverse (backward,
+    handing the input gradient up the line) equals the unsplit network."""
+    wl = tiny_resnet(K=3)
+    mods = [[torch.as_tensor(p, dtype=DT) for p in m] for m in make_params(wl, 1)]
+    x, y = make_batch(wl, 1, 0, 0)
+    grads, loss = fdg.definition_gradient(wl.ops, wl.bounds, mods, x, y)
+    flat = [p for m in mods for p in m]
+    ref_loss, ref = _autograd_net(wl.ops, flat, torch.as_tensor(x, dtype=DT), y)
+    assert abs(float(loss) - ref_loss) < 1e-12
+    for g1, g2 in zip([g for m in grads for g in m], ref):
+        assert torch.allclose(g1, g2, rtol=1e-10, atol=1e-12)
+
+
+def test_input_gradient_of_a_module_matches_autograd():
+    wl = tiny_resnet(K=2)
+    mods = [[torch.as_tensor(p, dtype=DT) for p in m] for m in make_params(wl, 2)]
+    ops1 = wl.ops[wl.bounds[1]:]
+    h = torch.randn(3, 8, 8, 8, dtype=DT, generator=torch.Generator().manual_seed(0))
+    y = np.array([1, 5, 9])
+    dlog, saved, _ = N.forward(ops1, mods[1], h, torch.as_tensor(y, dtype=torch.int64))
+    dx, _ = N.backward(ops1, mods[1], saved, dlog, need_dx=True)
+    ha = h.clone().requires_grad_()
+    ps = [p.clone() for p in mods[1]]
+    slots = N.param_slots(ops1)
+    # reuse the autograd net with the input requiring grad
+    hh, stack = ha, []
+    for op, s in zip(ops1, slots):
+        k = op["op"]
+        if k == "conv":
+            hh = F.conv2d(hh, ps[s], ps[s + 1], stride=op["stride"], padding=op["pad"])
+        elif k == "linear":
+            hh = F.linear(hh.flatten(1), ps[s], ps[s + 1]).view(hh.shape[0], -1, 1, 1)
+        elif k == "relu":
+            hh = F.relu(hh)
+        elif k == "gap":
+            hh = F.adaptive_avg_pool2d(hh, 1)
+        elif k == "res_begin":
+            stack.append(hh)
+        elif k == "res_add":
+            xin = stack.pop()
+            sc = op["shortcut"]
+            short = F.conv2d(xin, ps[s], ps[s + 1], stride=sc["stride"], padding=sc["pad"]) if sc else xin
+            hh = short + op["scale"] * hh
+        elif k == "softmax_ce":
+            hh = F.cross_entropy(hh.flatten(1), torch.as_tensor(y, dtype=torch.int64))
+    hh.backward()
+    assert torch.allclose(dx, ha.grad, rtol=1e-10, atol=1e-13)
