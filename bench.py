@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the decoupled data-parallel training step on one MI355X.
+
+A step is one dds_step: every module's forward, backward, replica-mean SGD update and
+weight snapshot for one batch of W*B synthetic CIFAR-shaped samples, inputs already in
+HBM. Prints ONE JSON line: samples/s plus the roofline record of the dominant kernel
+class and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2500.0, "f32": 157.3}  # dense MFMA TFLOP/s of MI355X
+
+
+def hip_event_timer():
+    """HIP events through libamdhip64 (works on any stream, unlike torch.cuda.Event)."""
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+    hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+    hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+    return hip
+
+
+def cpu_baseline(wl, seconds_budget=20.0):
+    """The oracle as it stands on a bounded sample: same K / W / delays / layers with a
+    reduced per-replica batch, timed over steady-state iterations."""
+    import torch
+    from dds_inputs import make_batch, make_params, workload
+    from oracle import fdg
+    small_b = {"cfg0_mlp": wl.B, "cfg1_cnn": 8, "cfg2_resnet18": 2, "cfg3_resnet56": 2, "cfg4_resnet34w": 1}.get(wl.name, 2)
+    small = workload(wl.name, B=small_b) if wl.name.startswith("cfg") else wl
+    pipe = fdg.Pipeline(small.ops, small.bounds, small.W, make_params(small, 0), small.lr, small.momentum)
+    pipe.keep_history = False
+    warm = 2 * (small.K - 1)
+    t_used, n = 0.0, 0
+    t = 0
+    while True:
+        batches = [make_batch(small, 0, t, s) for s in range(small.W)]
+        t0 = time.perf_counter()
+        pipe.step(batches)
+        dt = time.perf_counter() - t0
+        if t >= warm:
+            t_used += dt
+            n += 1
+            if t_used > seconds_budget or n >= 50:
+                break
+        t += 1
+    sps = n * small.W * small.B / t_used
+    return {"value": sps, "unit": "samples/s", "cores": torch.get_num_threads(), "kind": "oracle",
+            "sample": f"{n} steady-state steps of {small.name} with per-replica batch {small.B} "
+                      f"(full K={small.K}, W={small.W}); fp64"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2_resnet18")
+    ap.add_argument("--batch", type=int, default=None, help="override per-replica batch (debug only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (all K x W module-replica pairs live on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2509_05679_amd as P
+    from dds_inputs import make_batch, make_params, workload
+
+    wl = workload(args.workload, B=args.batch)
+    warmup = args.warmup if args.warmup is not None else 2 * (wl.K - 1) + 5
+    warmup = max(warmup, 2 * (wl.K - 1))  # timed steps are steady state: every module forwards, backwards, updates
+    spec = P.Spec.from_workload(wl)
+    tr = P.Trainer(spec, wl.W)
+    init = make_params(wl, 0)
+    for k0 in range(wl.K):
+        tr.dds_set_params(k0, init[k0])
+    # a small pool of resident synthetic batches, cycled
+    pool = 4
+    xs = [[torch.from_numpy(make_batch(wl, 0, t, s)[0]).cuda() for s in range(wl.W)] for t in range(pool)]
+    ys = [[torch.from_numpy(make_batch(wl, 0, t, s)[1]).cuda() for s in range(wl.W)] for t in range(pool)]
+    stream = torch.cuda.current_stream()
+    for t in range(warmup):
+        tr.dds_step(xs[t % pool], ys[t % pool])
+    torch.cuda.synchronize()
+
+    hip = hip_event_timer()
+    e0, e1 = ctypes.c_void_p(), ctypes.c_void_p()
+    hip.hipEventCreate(ctypes.byref(e0))
+    hip.hipEventCreate(ctypes.byref(e1))
+    sp = ctypes.c_void_p(stream.cuda_stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    hip.hipEventRecord(e0, sp)
+    for t in range(args.steps):
+        tr.dds_step(xs[(warmup + t) % pool], ys[(warmup + t) % pool])
+    hip.hipEventRecord(e1, sp)
+    hip.hipEventSynchronize(e1)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = ctypes.c_float()
+    hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1)
+    ms_per_step = ms.value / args.steps
+    loss = tr.dds_get_loss()
+    samples = wl.W * wl.B
+    flops = tr.dds_gemm_flops_per_step()
+    launches = tr.dds_launches_last_step()
+
+    # roofline of the dominant kernel class (the MFMA implicit-GEMM kernels): algorithmic
+    # FLOPs of all conv/linear forward+dgrad+wgrad launches of a step over the step time
+    # measured here with HIP events. The step also contains the bandwidth-bound kernels, so
+    # this is a lower bound on the GEMM kernels' own rate (per-kernel times: profiles/).
+    achieved = flops / (ms_per_step * 1e-3) / 1e12
+    peak = PEAK[wl.precision]
+    out = {
+        "metric": "training samples/sec on 1 MI355X per decoupled step",
+        "value": samples / (ms_per_step * 1e-3),
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.precision == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: K={wl.K} modules, W={wl.W} replicas x batch {wl.B}, {wl.precision}",
+                   "launches_per_step": launches, "wall_ms_per_step": wall * 1e3 / args.steps,
+                   "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30},
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": None,
+                     "note": "conv/linear fwd+dgrad+wgrad algorithmic FLOPs per step over the whole step time"},
+    }
+    tr.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,148 @@
+/*
+ * dds — one training iteration of data parallelism combined with fully decoupled
+ * parallel backpropagation (stale gradients), for one MI355X (gfx950).
+ *
+ * The network (L layers) is split into K contiguous modules; W data-groups
+ * ("replicas") each feed their own mini-batch of B samples per iteration.
+ * At iteration t module k0 (zero-based)
+ *   - forwards the mini-batch sampled at t-k0 with its current weights,
+ *   - back-propagates the mini-batch sampled at t-k0-2*d[k0] with the weights it
+ *     held at that batch's forward and the error gradient module k0+1 produced in
+ *     an earlier iteration,
+ *   - applies  w <- w - lr * (1/W) sum_s g_s  (g_s = mean gradient over replica s's
+ *     mini-batch); no update while the backward batch index is negative.
+ * (Paper: Section 3.2 forward/backward schedule; Section 3.3 update (a)/(b) with the
+ *  mixing matrix P = (1/S) 1 1^T; Algorithm 1, Appendix D.)
+ *
+ * All pointers named "device" must be device memory of the current HIP device (or
+ * host memory the device can address). The library never allocates device memory:
+ * the caller provides one arena. All work is enqueued on the stream passed in; side
+ * streams used internally are forked from and joined to it with events.
+ * Every function returns DDS_OK (0) or a negative error code; dds_last_error()
+ * returns a thread-local message for the last failing call. No C++ exceptions cross
+ * this boundary. A context is not thread-safe.
+ */
+#ifndef DDS_H_
+#define DDS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DDS_OK = 0,
+  DDS_EINVAL = -1,       /* malformed spec / K / W / delays / arguments */
+  DDS_ENOMEM = -2,       /* arena too small */
+  DDS_EHIP = -3,         /* a HIP runtime call failed */
+  DDS_EUNSUPPORTED = -4  /* valid request the kernels do not cover */
+};
+
+/* Layer kinds A_l (Section 2.1: h_l = A_l(h_{l-1}, w_l)). */
+enum {
+  DDS_OP_CONV2D = 1,    /* cin,cout,ksize,stride,pad; square kernel; has a bias */
+  DDS_OP_LINEAR = 2,    /* cin,cout; input must be [N,cin,1,1]; has a bias */
+  DDS_OP_RELU = 3,      /* must directly follow CONV2D, LINEAR or RES_ADD */
+  DDS_OP_MAXPOOL2 = 4,  /* 2x2 window, stride 2; gradient goes to the first maximum */
+  DDS_OP_GAP = 5,       /* global average pool to [N,C,1,1] */
+  DDS_OP_RES_BEGIN = 6, /* marks the residual block input x */
+  DDS_OP_RES_ADD = 7,   /* y = shortcut(x) + res_scale * y_main. cout == 0: identity
+                           shortcut; else a conv(cin,cout,ksize,stride,pad)+bias */
+  DDS_OP_SOFTMAX_CE = 8 /* mean softmax cross-entropy; must be the last layer */
+};
+
+enum { DDS_F32 = 0, DDS_BF16_F32MASTER = 1 };
+
+typedef struct dds_layer {
+  int32_t op;
+  int32_t cin, cout, ksize, stride, pad;
+  float res_scale;
+  int32_t reserved;
+} dds_layer;
+
+typedef struct dds_spec {
+  int32_t n_layers;
+  const dds_layer* layers; /* host; n_layers entries */
+  const int32_t* bounds;   /* host; K+1 indices: module k0 owns layers[bounds[k0]..bounds[k0+1]) */
+  int32_t in_c, in_h, in_w; /* one sample as the caller stores it (NCHW, fp32) */
+  int32_t classes;
+  int32_t batch;           /* B: samples per replica per iteration */
+  int32_t precision;       /* DDS_F32 | DDS_BF16_F32MASTER */
+  float lr;                /* default step size (see dds_step) */
+  float momentum;          /* 0 = plain SGD; else v <- mu v + g, w <- w - lr v */
+} dds_spec;
+
+typedef struct dds_ctx dds_ctx;
+
+/* Integers that drive iteration t (Section 3.2 closed forms). Pure host function, no
+ * GPU needed. delays: K per-leg delays d[k0] or NULL for the paper's d[k0] = K-1-k0.
+ * out: K records of DDS_SCHED_INTS int32 each:
+ *   [0] f = t-k0            mini-batch forwarded (negative: idle)
+ *   [1] b = t-k0-2d[k0]     mini-batch back-propagated (negative: idle, no update)
+ *   [2] ring depth R = 2d[k0]+1 (saved activations and weight snapshots)
+ *   [3] slot written by the forward      = t mod R
+ *   [4] slot read by the backward        = (t-2d[k0]) mod R
+ *   [5] error-mailbox slot read  (gradient sent by module k0+1), -1 for the last module
+ *   [6] error-mailbox slot written (gradient sent to module k0-1), -1 for module 0
+ *   [7] label-queue slot read by the last module's forward, -1 otherwise
+ * Returns DDS_EINVAL if delays violate d[K-1] >= 0, d[k0] >= d[k0+1]+1. */
+#define DDS_SCHED_INTS 8
+int dds_schedule(int K, const int* delays, int64_t t, int32_t* out);
+
+/* Bytes of arena dds_create needs for this problem (host computation only). */
+int dds_arena_bytes(const dds_spec* spec, int K, int W, const int* delays, size_t* bytes);
+
+/* Builds a context inside the caller's arena (device memory, 256-byte aligned, at
+ * least dds_arena_bytes bytes, owned by the caller and kept alive until
+ * dds_destroy). Zeroes the arena: all weights are zero until dds_set_params
+ * is called. Errors: DDS_EINVAL (spec, K, W in [1,32], delays),
+ * DDS_EUNSUPPORTED (layer pattern the kernels do not cover), DDS_ENOMEM, DDS_EHIP. */
+int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* arena_device,
+               size_t arena_bytes, dds_ctx** out);
+
+int dds_destroy(dds_ctx* ctx);
+
+/* Number of fp32 parameters of a module in canonical order: for every CONV2D /
+ * LINEAR / RES_ADD-with-projection in layer order, weight [cout,cin,k,k] (linear:
+ * [cout,cin]) then bias [cout]. Negative error code on failure. */
+int64_t dds_param_count(const dds_ctx* ctx, int module);
+
+/* Copies a module's fp32 master weights to / from dst / src (device-addressable,
+ * n_floats == dds_param_count) in canonical order, asynchronously on stream.
+ * dds_set_params also refreshes the compute-precision copy and every weight
+ * snapshot of the module and clears its momentum; call it before the first step
+ * (Algorithm 1 input: the initial weights, identical in every data-group). */
+int dds_get_params(dds_ctx* ctx, int module, float* dst_device, size_t n_floats, void* hip_stream);
+int dds_set_params(dds_ctx* ctx, int module, const float* src_device, size_t n_floats, void* hip_stream);
+
+/* One iteration t of every module (Algorithm 1 loop body for all S*K agents).
+ * x_device[s]: replica s's mini-batch, fp32 [B,in_c,in_h,in_w] (NCHW);
+ * y_device[s]: its targets, int32 [B], values in [0,classes). Both arrays of
+ * pointers are host arrays of W device pointers, borrowed: they are read only by the
+ * ingest kernel enqueued by this call. lr: step size for this iteration, or NaN to
+ * use spec.lr. Asynchronous on stream. */
+int dds_step(dds_ctx* ctx, const float* const* x_device, const int32_t* const* y_device, float lr,
+             void* hip_stream);
+
+/* Mean loss of the mini-batch the last module forwarded in the latest step (sampled
+ * K-1 iterations earlier): mean over each replica's B samples, then over replicas.
+ * Synchronises stream. DDS_EINVAL if no loss exists yet (fewer than K steps). */
+int dds_get_loss(dds_ctx* ctx, float* host_out, void* hip_stream);
+
+/* Iterations executed so far. */
+int64_t dds_step_count(const dds_ctx* ctx);
+
+/* Introspection for tests and the benchmark (host only): number of kernel launches
+ * of the latest step, and per-step algorithmic FLOPs of the conv/linear kernels
+ * (2*M*N*K over forward, dgrad and wgrad launches of a steady-state step). */
+int64_t dds_launches_last_step(const dds_ctx* ctx);
+double dds_gemm_flops_per_step(const dds_ctx* ctx);
+
+const char* dds_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DDS_H_ */

@@ -53,7 +53,7 @@ def schedule(t: int, K: int, d: Optional[Sequence[int]] = None) -> List[dict]:
     fwd_slot = t mod R is written by the forward, bwd_slot = (t-2d) mod R is read
     by the backward; err_depth / err_write / err_read index the error-gradient
     mailbox between module k0+1 (writer) and k0 (reader); label_slot indexes the
-    depth-K queue of targets travelling to the last module."""
+    queue (depth K + 2 d[K-1]) of targets travelling to the last module."""
     d = paper_delays(K) if d is None else list(d)
     out = []
     for k0 in range(K):
@@ -74,7 +74,7 @@ def schedule(t: int, K: int, d: Optional[Sequence[int]] = None) -> List[dict]:
             rec["err_write"] = t % (lag_up + 1)
         else:
             rec["err_write"] = -1
-        rec["label_slot"] = (f % K) if (k0 == K - 1 and f >= 0) else -1
+        rec["label_slot"] = (f % (K + 2 * d[K - 1])) if (k0 == K - 1 and f >= 0) else -1
         out.append(rec)
     return out
 

@@ -1,0 +1,924 @@
+// Host engine of libdds: validates the layer spec, fuses it into kernel nodes, lays
+// the arena out (activation rings, weight snapshots, error mailboxes, gradient
+// partials, master weights) and enqueues one training iteration per dds_step.
+//
+// Data flow (Section 3.2 / Algorithm 1 of the paper): at iteration t module k0
+// forwards batch t-k0 into ring slot t mod R, back-propagates batch t-k0-2d from
+// ring slot (t-2d) mod R with the transposed weight snapshot of the same slot and
+// the error gradient module k0+1 left in the mailbox, then applies the replica-mean
+// SGD update and snapshots the new weights into slot (t+1) mod R. A module reads its
+// input activation directly from the ring of the module below (no copy): that slot
+// stays live two iterations longer than the reader needs it.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "../../include/dds.h"
+#include "kernels.h"
+
+using namespace dds;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                      \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) return fail(DDS_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int round_up(int x, int a) { return (x + a - 1) / a * a; }
+
+constexpr int G_NONE = -1;     // no gradient wanted
+constexpr int G_ERR_IN = -2;   // mailbox filled by module k0+1 (gradient of this module's output)
+constexpr int G_ERR_OUT = -3;  // mailbox read by module k0-1 (gradient of this module's input)
+
+enum TensorKind { T_RING, T_TEMP, T_EXTERNAL };
+enum NodeKind { N_CONV, N_MAXPOOL, N_GAP, N_CE };
+
+struct Tensor {
+  int C = 0, Cpad = 0, H = 0, W = 0;
+  int dt = DT_F32;
+  int kind = T_RING;
+  bool relu_out = false;
+  size_t bytes = 0;     // whole mini-batch of all replicas
+  size_t ring_off = 0;  // offset inside a ring slot (T_RING)
+  char* temp = nullptr; // T_TEMP storage
+  int grad = G_NONE;    // gradient buffer id
+};
+
+struct ParamLayer {
+  int Cout, Cin, R, RS, Cinpad, Coutpad, stride, pad;
+  long long n;        // Cout*RS*Cinpad + Cout
+  long long pstride;  // n rounded up to 4
+  long long off;      // element offset in the module's master array
+  int nsplit = 0;
+  bool need_stash = false;
+  float* partial = nullptr;
+  char* stash = nullptr;  // [R_k][Cin*RS*Coutpad] compute dtype
+  long long stash_elems = 0;
+};
+
+struct Node {
+  int kind;
+  int in = -1, out = -1;
+  int layer = -1;
+  bool relu = false;
+  int res = -1;       // tensor added in the forward epilogue
+  float alpha = 1.f;
+  int gout = G_NONE, gin = G_NONE, addend = G_NONE;
+  bool mask_in = false;
+  bool out_f32 = false;
+};
+
+struct GradBuf {
+  size_t bytes = 0;
+  char* ptr = nullptr;
+};
+
+struct Module {
+  int k0 = 0, d = 0, R = 1;
+  std::vector<Tensor> tensors;
+  std::vector<Node> nodes;
+  std::vector<ParamLayer> layers;  // canonical (spec) order
+  std::vector<GradBuf> grads;
+  size_t slot_bytes = 0;
+  char* ring = nullptr;
+  long long n_master = 0;  // floats
+  float* master = nullptr;
+  float* momentum = nullptr;
+  char* work = nullptr;    // compute-precision copy (bf16 path)
+  // error mailbox written by module k0+1, read by this module
+  int err_depth = 0;
+  size_t err_bytes = 0;
+  char* err = nullptr;
+  UpdateDesc* descs_dev = nullptr;
+  int* map_update_dev = nullptr;
+  int* map_stash_dev = nullptr;
+  int blocks_update = 0, blocks_stash = 0;
+  int out_tensor = -1;
+  long long canon_params = 0;
+  hipStream_t stream = nullptr;
+  hipEvent_t done = nullptr;
+};
+
+struct Arena {
+  char* base = nullptr;
+  size_t size = 0, used = 0;
+  bool dry = true;
+  char* take(size_t bytes) {
+    size_t off = align_up(used, 256);
+    used = off + bytes;
+    if (dry) return nullptr;
+    return base + off;
+  }
+};
+
+}  // namespace
+
+struct dds_ctx {
+  int K = 0, W = 0, B = 0, N = 0;
+  int dt = DT_F32;
+  int classes = 0;
+  int in_c = 0, in_h = 0, in_w = 0;
+  float lr = 0.f, mu = 0.f;
+  std::vector<int> d;
+  std::vector<Module> mods;
+  int label_depth = 0;
+  int32_t* labels = nullptr;  // [label_depth][N]
+  float* loss = nullptr;      // [W]
+  int64_t t = 0;
+  bool have_loss = false;
+  hipEvent_t fork = nullptr;
+  int64_t launches = 0;
+  double gemm_flops = 0.0;
+  size_t arena_used = 0;
+};
+
+namespace {
+
+int check_delays(int K, const int* delays, std::vector<int>& d) {
+  d.resize(K);
+  for (int k = 0; k < K; ++k) d[k] = delays ? delays[k] : K - 1 - k;
+  if (d[K - 1] < 0) return fail(DDS_EINVAL, "delay of the last module must be >= 0");
+  for (int k = 0; k + 1 < K; ++k)
+    if (d[k] < d[k + 1] + 1)
+      return fail(DDS_EINVAL, "delays[%d]=%d must be >= delays[%d]+1=%d (the error gradient arrives one iteration later)",
+                  k, d[k], k + 1, d[k + 1] + 1);
+  return DDS_OK;
+}
+
+// --------------------------------------------------------------------------- planning
+int new_tensor(Module& m, int N, int C, int H, int W, int dt, int kind) {
+  Tensor t;
+  t.C = C;
+  t.Cpad = round_up(C, dtype_ce(dt));
+  t.H = H;
+  t.W = W;
+  t.dt = dt;
+  t.kind = kind;
+  t.bytes = (size_t)N * H * W * t.Cpad * dtype_size(dt);
+  m.tensors.push_back(t);
+  return (int)m.tensors.size() - 1;
+}
+
+int add_layer(Module& m, int cin, int cout, int ksize, int stride, int pad, int dt) {
+  ParamLayer L;
+  L.Cout = cout;
+  L.Cin = cin;
+  L.R = ksize;
+  L.RS = ksize * ksize;
+  L.Cinpad = round_up(cin, dtype_ce(dt));
+  L.Coutpad = round_up(cout, dtype_ce(dt));
+  L.stride = stride;
+  L.pad = pad;
+  L.n = (long long)cout * L.RS * L.Cinpad + cout;
+  L.pstride = (L.n + 3) / 4 * 4;
+  L.off = m.n_master;
+  m.n_master += (L.n + 63) / 64 * 64;
+  m.canon_params += (long long)cout * cin * L.RS + cout;
+  m.layers.push_back(L);
+  return (int)m.layers.size() - 1;
+}
+
+int conv_out(int h, int k, int stride, int pad) { return (h + 2 * pad - k) / stride + 1; }
+
+// Parses module k0's slice of the spec into fused nodes. in_* describe its input tensor.
+int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* input, Module& m) {
+  const int lo = sp.bounds[k0], hi = sp.bounds[k0 + 1];
+  // tensor 0 = module input
+  {
+    if (k0 == 0) {
+      new_tensor(m, N, sp.in_c, sp.in_h, sp.in_w, dt, T_RING);
+      m.tensors[0].grad = G_NONE;
+    } else {
+      Tensor t0 = *input;
+      t0.kind = T_EXTERNAL;
+      t0.grad = G_ERR_OUT;
+      m.tensors.push_back(t0);
+    }
+  }
+  int cur = 0;
+  int res_in = -1;  // block input tensor while inside a residual block
+  for (int i = lo; i < hi; ++i) {
+    const dds_layer& L = sp.layers[i];
+    const bool next_is = i + 1 < hi;
+    switch (L.op) {
+      case DDS_OP_CONV2D:
+      case DDS_OP_LINEAR: {
+        const bool lin = L.op == DDS_OP_LINEAR;
+        const int ks = lin ? 1 : L.ksize, st = lin ? 1 : L.stride, pd = lin ? 0 : L.pad;
+        const Tensor ti = m.tensors[cur];
+        if (L.cin != ti.C) return fail(DDS_EINVAL, "layer %d: cin=%d but the incoming tensor has %d channels", i, L.cin, ti.C);
+        if (lin && (ti.H != 1 || ti.W != 1)) return fail(DDS_EUNSUPPORTED, "layer %d: LINEAR needs a [N,C,1,1] input (insert GAP)", i);
+        if (L.cout < 1 || ks < 1 || (st != 1 && st != 2) || pd < 0 || pd >= ks)
+          return fail(DDS_EUNSUPPORTED, "layer %d: conv needs cout>=1, stride 1 or 2, 0<=pad<ksize", i);
+        const int Ho = conv_out(ti.H, ks, st, pd), Wo = conv_out(ti.W, ks, st, pd);
+        if (Ho < 1 || Wo < 1) return fail(DDS_EINVAL, "layer %d: empty output", i);
+        Node nd;
+        nd.kind = N_CONV;
+        nd.in = cur;
+        nd.layer = add_layer(m, L.cin, L.cout, ks, st, pd, dt);
+        int nxt = i + 1;
+        bool fuse_res = nxt < hi && sp.layers[nxt].op == DDS_OP_RES_ADD;
+        bool to_ce = nxt < hi && sp.layers[nxt].op == DDS_OP_SOFTMAX_CE;
+        const int odt = to_ce ? DT_F32 : dt;
+        int out = new_tensor(m, N, L.cout, Ho, Wo, odt, T_RING);
+        if (to_ce) {  // logits: fp32 values, padded like a compute-precision tensor so dlogits can mirror it
+          Tensor& lt = m.tensors[out];
+          lt.Cpad = round_up(L.cout, dtype_ce(dt));
+          lt.bytes = (size_t)N * lt.Cpad * 4;
+          nd.out_f32 = true;
+        }
+        nd.out = out;
+        Node sc_node;
+        bool have_sc = false;
+        if (fuse_res) {
+          if (res_in < 0) return fail(DDS_EINVAL, "layer %d: RES_ADD without RES_BEGIN", nxt);
+          const dds_layer& A = sp.layers[nxt];
+          const Tensor tx = m.tensors[res_in];
+          nd.alpha = A.res_scale;
+          if (A.cout > 0) {
+            if (A.cin != tx.C || A.cout != L.cout) return fail(DDS_EINVAL, "layer %d: shortcut conv shape mismatch", nxt);
+            if (A.ksize < 1 || (A.stride != 1 && A.stride != 2) || A.pad < 0 || A.pad >= A.ksize)
+              return fail(DDS_EUNSUPPORTED, "layer %d: shortcut conv needs stride 1 or 2, 0<=pad<ksize", nxt);
+            if (conv_out(tx.H, A.ksize, A.stride, A.pad) != Ho || conv_out(tx.W, A.ksize, A.stride, A.pad) != Wo)
+              return fail(DDS_EINVAL, "layer %d: shortcut output size differs from the main path", nxt);
+            sc_node.kind = N_CONV;
+            sc_node.in = res_in;
+            sc_node.out = new_tensor(m, N, A.cout, Ho, Wo, dt, T_TEMP);
+            have_sc = true;
+            nd.res = sc_node.out;
+          } else {
+            if (tx.C != L.cout || tx.H != Ho || tx.W != Wo)
+              return fail(DDS_EINVAL, "layer %d: identity shortcut needs equal shapes", nxt);
+            nd.res = res_in;
+          }
+          ++nxt;
+        }
+        if (nxt < hi && sp.layers[nxt].op == DDS_OP_RELU) {
+          nd.relu = true;
+          m.tensors[out].relu_out = true;
+          ++nxt;
+        }
+        if (have_sc) {
+          // canonical order: main-path convs first, then the projection (it sits at RES_ADD)
+          const dds_layer& A = sp.layers[i + 1];
+          sc_node.layer = add_layer(m, A.cin, A.cout, A.ksize, A.stride, A.pad, dt);
+          m.nodes.push_back(sc_node);  // runs before the conv whose epilogue adds it
+        }
+        m.nodes.push_back(nd);
+        if (fuse_res) res_in = -1;
+        cur = out;
+        i = nxt - 1;
+        break;
+      }
+      case DDS_OP_RELU:
+        return fail(DDS_EUNSUPPORTED, "layer %d: RELU must directly follow CONV2D, LINEAR or RES_ADD", i);
+      case DDS_OP_MAXPOOL2: {
+        const Tensor ti = m.tensors[cur];
+        if (ti.H % 2 || ti.W % 2) return fail(DDS_EUNSUPPORTED, "layer %d: MAXPOOL2 needs even height and width", i);
+        Node nd;
+        nd.kind = N_MAXPOOL;
+        nd.in = cur;
+        nd.out = new_tensor(m, N, ti.C, ti.H / 2, ti.W / 2, dt, T_RING);
+        m.nodes.push_back(nd);
+        cur = nd.out;
+        break;
+      }
+      case DDS_OP_GAP: {
+        const Tensor ti = m.tensors[cur];
+        Node nd;
+        nd.kind = N_GAP;
+        nd.in = cur;
+        nd.out = new_tensor(m, N, ti.C, 1, 1, dt, T_RING);
+        m.nodes.push_back(nd);
+        cur = nd.out;
+        break;
+      }
+      case DDS_OP_RES_BEGIN:
+        if (res_in >= 0) return fail(DDS_EUNSUPPORTED, "layer %d: nested residual blocks", i);
+        res_in = cur;
+        break;
+      case DDS_OP_RES_ADD:
+        return fail(DDS_EUNSUPPORTED, "layer %d: RES_ADD must directly follow the block's last CONV2D", i);
+      case DDS_OP_SOFTMAX_CE: {
+        if (k0 != K - 1 || i != sp.n_layers - 1) return fail(DDS_EINVAL, "layer %d: SOFTMAX_CE must be the last layer", i);
+        const Tensor ti = m.tensors[cur];
+        if (ti.dt != DT_F32 || ti.C != sp.classes || ti.H != 1 || ti.W != 1)
+          return fail(DDS_EUNSUPPORTED, "layer %d: SOFTMAX_CE must follow a LINEAR/CONV2D producing [N,classes,1,1]", i);
+        Node nd;
+        nd.kind = N_CE;
+        nd.in = cur;
+        m.nodes.push_back(nd);
+        break;
+      }
+      default:
+        return fail(DDS_EINVAL, "layer %d: unknown op %d", i, L.op);
+    }
+    (void)next_is;
+  }
+  if (res_in >= 0) return fail(DDS_EINVAL, "module %d ends inside a residual block", k0);
+  if (k0 == K - 1) {
+    if (m.nodes.empty() || m.nodes.back().kind != N_CE) return fail(DDS_EINVAL, "the last layer must be SOFTMAX_CE");
+  } else if (m.tensors[cur].dt != dt) {
+    return fail(DDS_EINVAL, "module %d: SOFTMAX_CE before the last module", k0);
+  }
+  m.out_tensor = cur;
+
+  // gradient buffers: one per tensor that a backward kernel writes
+  for (size_t ti = 1; ti < m.tensors.size(); ++ti) {
+    Tensor& t = m.tensors[ti];
+    if (t.kind == T_TEMP) continue;  // projection output: shares the block output's gradient
+    if ((int)ti == m.out_tensor && k0 < K - 1) { t.grad = G_ERR_IN; continue; }
+    GradBuf g;
+    g.bytes = t.dt == dt ? t.bytes : (size_t)N * t.Cpad * dtype_size(dt);  // dlogits in compute precision
+    m.grads.push_back(g);
+    t.grad = (int)m.grads.size() - 1;
+  }
+  for (size_t ni = 0; ni < m.nodes.size(); ++ni) {
+    Node& nd = m.nodes[ni];
+    if (nd.kind == N_CE) { nd.gout = G_NONE; nd.gin = m.tensors[nd.in].grad; continue; }
+    const Tensor& to = m.tensors[nd.out];
+    nd.gin = m.tensors[nd.in].grad;
+    nd.mask_in = m.tensors[nd.in].relu_out;
+    if (to.kind == T_TEMP) {
+      // projection shortcut: find the conv that consumes it
+      for (size_t nj = ni + 1; nj < m.nodes.size(); ++nj)
+        if (m.nodes[nj].kind == N_CONV && m.nodes[nj].res == nd.out) { nd.gout = m.tensors[m.nodes[nj].out].grad; break; }
+      if (nd.gin != G_NONE) {  // its input gradient goes to a scratch buffer the block's first conv adds
+        GradBuf g;
+        g.bytes = m.tensors[nd.in].bytes;
+        m.grads.push_back(g);
+        nd.gin = (int)m.grads.size() - 1;
+        nd.mask_in = false;
+      }
+    } else {
+      nd.gout = to.grad;
+    }
+  }
+  // residual wiring: the first conv of a block adds the shortcut's gradient
+  for (size_t ni = 0; ni < m.nodes.size(); ++ni) {
+    Node& nd = m.nodes[ni];
+    if (nd.kind != N_CONV || nd.res < 0) continue;
+    const Tensor& tr = m.tensors[nd.res];
+    int block_in;
+    int shortcut_grad;
+    if (tr.kind == T_TEMP) {
+      const Node* sc = nullptr;
+      for (size_t nj = 0; nj < ni; ++nj)
+        if (m.nodes[nj].out == nd.res) sc = &m.nodes[nj];
+      block_in = sc->in;
+      shortcut_grad = sc->gin;
+    } else {
+      block_in = nd.res;
+      shortcut_grad = nd.gout;
+    }
+    // first node after the block input that consumes it on the main path
+    Node* first = nullptr;
+    for (size_t nj = 0; nj <= ni; ++nj)
+      if (m.nodes[nj].in == block_in && m.tensors[m.nodes[nj].out].kind != T_TEMP) { first = &m.nodes[nj]; break; }
+    if (!first || first->kind != N_CONV) return fail(DDS_EUNSUPPORTED, "a residual block must start with CONV2D");
+    if (first == &nd) return fail(DDS_EUNSUPPORTED, "a residual block needs at least two convolutions");
+    if (first->gin != G_NONE) first->addend = shortcut_grad;
+  }
+  for (Node& nd : m.nodes)
+    if (nd.kind == N_CONV && nd.gin != G_NONE) m.layers[nd.layer].need_stash = true;
+  return DDS_OK;
+}
+
+int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
+  const int es = dtype_size(c.dt);
+  for (int k0 = 0; k0 < c.K; ++k0) {
+    Module& m = c.mods[k0];
+    // ring: R slots of every saved tensor
+    size_t off = 0;
+    for (Tensor& t : m.tensors)
+      if (t.kind == T_RING) { t.ring_off = off; off = align_up(off + t.bytes, 256); }
+    m.slot_bytes = off;
+    m.ring = A.take(m.slot_bytes * m.R);
+    for (Tensor& t : m.tensors)
+      if (t.kind == T_TEMP) t.temp = A.take(t.bytes);
+    for (GradBuf& g : m.grads) g.ptr = A.take(g.bytes);
+    m.master = (float*)A.take((size_t)m.n_master * 4);
+    if (c.mu != 0.f) m.momentum = (float*)A.take((size_t)m.n_master * 4);
+    if (c.dt == DT_BF16) m.work = A.take((size_t)m.n_master * es);
+    for (Node& nd : m.nodes) {
+      if (nd.kind != N_CONV) continue;
+      ParamLayer& L = m.layers[nd.layer];
+      const Tensor& to = m.tensors[nd.out];
+      const int P = c.N * to.H * to.W;
+      L.nsplit = wgrad_choose_split(c.dt, L.Cout, L.RS * L.Cinpad, P, c.W);
+      L.partial = (float*)A.take((size_t)L.nsplit * L.pstride * 4);
+      if (L.need_stash) {
+        L.stash_elems = (long long)L.Cin * L.RS * L.Coutpad;
+        L.stash = A.take(align_up((size_t)L.stash_elems * es, 256) * m.R);
+      }
+    }
+    if (k0 < c.K - 1) {
+      const int lag = 2 * (c.d[k0] - c.d[k0 + 1]) - 1;
+      m.err_depth = lag + 1;
+      m.err_bytes = align_up(m.tensors[m.out_tensor].bytes, 256);
+      m.err = A.take(m.err_bytes * m.err_depth);
+    }
+    // descriptor tables
+    int nb_u = 0, nb_s = 0;
+    for (ParamLayer& L : m.layers) {
+      nb_u += (int)((L.n + 1023) / 1024);
+      if (L.need_stash) nb_s += (int)((L.stash_elems + 1023) / 1024);
+    }
+    m.blocks_update = nb_u;
+    m.blocks_stash = nb_s;
+    m.descs_dev = (UpdateDesc*)A.take(sizeof(UpdateDesc) * m.layers.size());
+    m.map_update_dev = (int*)A.take(sizeof(int) * 2 * (nb_u > 0 ? nb_u : 1));
+    m.map_stash_dev = (int*)A.take(sizeof(int) * 2 * (nb_s > 0 ? nb_s : 1));
+  }
+  c.label_depth = c.K + 2 * c.d[c.K - 1];
+  c.labels = (int32_t*)A.take(sizeof(int32_t) * c.N * c.label_depth);
+  c.loss = (float*)A.take(sizeof(float) * c.W);
+  (void)sp;
+  return DDS_OK;
+}
+
+int build(dds_ctx& c, const dds_spec* sp, int K, int W, const int* delays) {
+  if (!sp || !sp->layers || !sp->bounds) return fail(DDS_EINVAL, "null spec");
+  if (K < 1 || K > 64) return fail(DDS_EINVAL, "K=%d out of range [1,64]", K);
+  if (W < 1 || W > 32) return fail(DDS_EINVAL, "W=%d out of range [1,32]", W);
+  if (sp->batch < 1 || sp->n_layers < 1 || sp->classes < 2 || sp->in_c < 1 || sp->in_h < 1 || sp->in_w < 1)
+    return fail(DDS_EINVAL, "bad batch / layer count / classes / input shape");
+  if (sp->precision != DDS_F32 && sp->precision != DDS_BF16_F32MASTER) return fail(DDS_EINVAL, "unknown precision");
+  if (!(sp->momentum >= 0.f && sp->momentum < 1.f)) return fail(DDS_EINVAL, "momentum must be in [0,1)");
+  if (sp->bounds[0] != 0 || sp->bounds[K] != sp->n_layers) return fail(DDS_EINVAL, "bounds must start at 0 and end at n_layers");
+  for (int k = 0; k < K; ++k)
+    if (sp->bounds[k + 1] <= sp->bounds[k]) return fail(DDS_EINVAL, "module %d is empty", k);
+  int rc = check_delays(K, delays, c.d);
+  if (rc) return rc;
+  if ((long long)W * sp->batch > (1 << 22)) return fail(DDS_EUNSUPPORTED, "W*B too large");
+  c.K = K;
+  c.W = W;
+  c.B = sp->batch;
+  c.N = W * sp->batch;
+  c.dt = sp->precision == DDS_F32 ? DT_F32 : DT_BF16;
+  c.classes = sp->classes;
+  c.in_c = sp->in_c;
+  c.in_h = sp->in_h;
+  c.in_w = sp->in_w;
+  c.lr = sp->lr;
+  c.mu = sp->momentum;
+  c.mods.assign(K, Module());
+  for (int k0 = 0; k0 < K; ++k0) {
+    Module& m = c.mods[k0];
+    m.k0 = k0;
+    m.d = c.d[k0];
+    m.R = 2 * m.d + 1;
+    const Tensor* in = k0 ? &c.mods[k0 - 1].tensors[c.mods[k0 - 1].out_tensor] : nullptr;
+    rc = plan_module(*sp, k0, K, c.N, c.dt, in, m);
+    if (rc) return rc;
+    bool has_params = !m.layers.empty();
+    (void)has_params;
+  }
+  // sizes that index arithmetic in the kernels keeps in 32 bits
+  for (Module& m : c.mods)
+    for (Tensor& t : m.tensors)
+      if ((long long)c.N * t.H * t.W > 0x7fffffffLL / 2 || t.bytes > ((size_t)1 << 40))
+        return fail(DDS_EUNSUPPORTED, "tensor too large");
+  return DDS_OK;
+}
+
+double count_flops(const dds_ctx& c) {
+  double f = 0;
+  for (const Module& m : c.mods)
+    for (const Node& nd : m.nodes) {
+      if (nd.kind != N_CONV) continue;
+      const ParamLayer& L = m.layers[nd.layer];
+      const Tensor& to = m.tensors[nd.out];
+      const double macs = (double)c.N * to.H * to.W * L.Cout * L.Cin * L.RS;
+      f += 2.0 * macs * (nd.gin != G_NONE ? 3 : 2);
+    }
+  return f;
+}
+
+// --------------------------------------------------------------------------- execution helpers
+struct Exec {
+  dds_ctx& c;
+  Module& m;
+  hipStream_t s;
+  int fslot, bslot;  // ring slots of the forward / backward batch
+  char* tensor_ptr(int ti, int slot) const {
+    const Tensor& t = m.tensors[ti];
+    if (t.kind == T_TEMP) return t.temp;
+    if (t.kind == T_RING) return m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
+    return nullptr;  // external handled by caller
+  }
+};
+
+char* input_ptr(dds_ctx& c, int k0, int64_t batch) {
+  // module k0 > 0 reads the output of module k0-1 for `batch`, forwarded there at iteration batch + k0 - 1
+  Module& up = c.mods[k0 - 1];
+  const int slot = (int)((batch + k0 - 1) % up.R);
+  return up.ring + (size_t)slot * up.slot_bytes + up.tensors[up.out_tensor].ring_off;
+}
+
+char* tptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
+  const Tensor& t = m.tensors[ti];
+  if (t.kind == T_TEMP) return t.temp;
+  if (t.kind == T_RING) return m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
+  return input_ptr(c, m.k0, batch);
+}
+
+char* gptr(dds_ctx& c, Module& m, int gid, int64_t t) {
+  if (gid >= 0) return m.grads[gid].ptr;
+  if (gid == G_ERR_IN) {
+    const int lag = m.err_depth - 1;
+    return m.err + (size_t)((t - lag) % m.err_depth) * m.err_bytes;
+  }
+  if (gid == G_ERR_OUT) {
+    Module& up = c.mods[m.k0 - 1];
+    return up.err + (size_t)(t % up.err_depth) * up.err_bytes;
+  }
+  return nullptr;
+}
+
+void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
+  const int slot = (int)(t % m.R);
+  const int es = dtype_size(c.dt);
+  for (const Node& nd : m.nodes) {
+    if (nd.kind == N_CE) continue;
+    const Tensor& ti = m.tensors[nd.in];
+    const Tensor& to = m.tensors[nd.out];
+    char* x = tptr(c, m, nd.in, slot, f);
+    char* y = tptr(c, m, nd.out, slot, f);
+    switch (nd.kind) {
+      case N_CONV: {
+        const ParamLayer& L = m.layers[nd.layer];
+        ConvParams p{};
+        p.x = x;
+        p.w = c.dt == DT_BF16 ? (const void*)(m.work + (size_t)L.off * es) : (const void*)(m.master + L.off);
+        p.y = y;
+        p.bias = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
+        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
+        p.mask = nullptr;
+        p.Nimg = c.N; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
+        p.Ho = to.H; p.Wo = to.W;
+        p.M = c.N * to.H * to.W;
+        p.Nout = L.Cout;
+        p.ldy = to.Cpad;
+        p.R = L.R; p.S = L.R; p.stride = L.stride; p.pad = L.pad;
+        p.Ktot = L.RS * L.Cinpad;
+        p.alpha = nd.alpha;
+        p.relu = nd.relu;
+        p.out_f32 = nd.out_f32;
+        p.dgrad = 0;
+        launch_conv(c.dt, p, s);
+        break;
+      }
+      case N_MAXPOOL:
+        launch_maxpool_fwd(c.dt, x, y, c.N, ti.H, ti.W, ti.Cpad, s);
+        break;
+      case N_GAP:
+        launch_gap_fwd(c.dt, x, y, c.N, ti.H * ti.W, ti.Cpad, s);
+        break;
+    }
+    ++c.launches;
+  }
+}
+
+void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
+  const int slot = (int)(((t - 2 * m.d) % m.R + m.R) % m.R);
+  const int es = dtype_size(c.dt);
+  for (int ni = (int)m.nodes.size() - 1; ni >= 0; --ni) {
+    const Node& nd = m.nodes[ni];
+    if (nd.kind == N_CE) continue;  // dlogits were produced by the loss kernel
+    const Tensor& ti = m.tensors[nd.in];
+    const Tensor& to = m.tensors[nd.out];
+    char* x = tptr(c, m, nd.in, slot, b);
+    char* gout = gptr(c, m, nd.gout, t);
+    char* gin = gptr(c, m, nd.gin, t);
+    switch (nd.kind) {
+      case N_CONV: {
+        const ParamLayer& L = m.layers[nd.layer];
+        const int ldg = nd.out_f32 ? to.Cpad : to.Cpad;
+        WgradParams w{};
+        w.dy = gout;
+        w.x = x;
+        w.partial = L.partial;
+        w.Nimg = c.N; w.H = ti.H; w.W = ti.W; w.Cx = ti.Cpad; w.Ho = to.H; w.Wo = to.W;
+        w.Mout = L.Cout;
+        w.ldy = ldg;
+        w.R = L.R; w.S = L.R; w.stride = L.stride; w.pad = L.pad;
+        w.NK = L.RS * L.Cinpad;
+        w.P = c.N * to.H * to.W;
+        w.nsplit = L.nsplit;
+        w.pix_per_split = w.P / L.nsplit;
+        w.Pl = L.pstride;
+        w.alpha = nd.alpha;
+        launch_wgrad(c.dt, w, s);
+        ++c.launches;
+        if (nd.gin != G_NONE) {
+          ConvParams p{};
+          p.x = gout;
+          p.w = L.stash + (size_t)slot * align_up((size_t)L.stash_elems * es, 256);
+          p.y = gin;
+          p.bias = nullptr;
+          p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
+          p.mask = nd.mask_in ? x : nullptr;
+          p.Nimg = c.N; p.H = to.H; p.W = to.W; p.Cx = ldg;
+          p.Ho = ti.H; p.Wo = ti.W;
+          p.M = c.N * ti.H * ti.W;
+          p.Nout = L.Cin;
+          p.ldy = ti.Cpad;
+          p.R = L.R; p.S = L.R; p.stride = L.stride; p.pad = L.pad;
+          p.Ktot = L.RS * L.Coutpad;
+          p.alpha = nd.alpha;
+          p.relu = 0;
+          p.out_f32 = 0;
+          p.dgrad = 1;
+          launch_conv(c.dt, p, s);
+          ++c.launches;
+        }
+        break;
+      }
+      case N_MAXPOOL:
+        if (nd.gin != G_NONE) {
+          launch_maxpool_bwd(c.dt, gout, x, gin, c.N, ti.H, ti.W, ti.Cpad, nd.mask_in, s);
+          ++c.launches;
+        }
+        break;
+      case N_GAP:
+        if (nd.gin != G_NONE) {
+          launch_gap_bwd(c.dt, gout, x, gin, c.N, ti.H * ti.W, ti.Cpad, nd.mask_in, s);
+          ++c.launches;
+        }
+        break;
+    }
+  }
+}
+
+int upload_tables(dds_ctx& c) {
+  const int es = dtype_size(c.dt);
+  for (Module& m : c.mods) {
+    std::vector<UpdateDesc> descs(m.layers.size());
+    std::vector<int> mu, ms;
+    for (size_t li = 0; li < m.layers.size(); ++li) {
+      const ParamLayer& L = m.layers[li];
+      UpdateDesc& d = descs[li];
+      d.master = m.master + L.off;
+      d.momentum = m.momentum ? m.momentum + L.off : nullptr;
+      d.partial = L.partial;
+      d.work = m.work ? (void*)(m.work + (size_t)L.off * es) : nullptr;
+      d.stash = L.stash;
+      d.stash_slot_elems = (long long)(align_up((size_t)L.stash_elems * es, 256) / es);
+      d.n = L.n;
+      d.pstride = L.pstride;
+      d.nsplit = L.nsplit;
+      d.Cout = L.Cout; d.RS = L.RS; d.Cinpad = L.Cinpad; d.Cin = L.Cin; d.Coutpad = L.Coutpad;
+      for (int b = 0; b < (int)((L.n + 1023) / 1024); ++b) { mu.push_back((int)li); mu.push_back(b); }
+      if (L.need_stash)
+        for (int b = 0; b < (int)((L.stash_elems + 1023) / 1024); ++b) { ms.push_back((int)li); ms.push_back(b); }
+    }
+    if (!descs.empty()) HIP_TRY(hipMemcpy(m.descs_dev, descs.data(), sizeof(UpdateDesc) * descs.size(), hipMemcpyHostToDevice));
+    if (!mu.empty()) HIP_TRY(hipMemcpy(m.map_update_dev, mu.data(), sizeof(int) * mu.size(), hipMemcpyHostToDevice));
+    if (!ms.empty()) HIP_TRY(hipMemcpy(m.map_stash_dev, ms.data(), sizeof(int) * ms.size(), hipMemcpyHostToDevice));
+  }
+  return DDS_OK;
+}
+
+}  // namespace
+
+// =========================================================================== C ABI
+extern "C" {
+
+const char* dds_last_error(void) { return g_err.c_str(); }
+
+int dds_schedule(int K, const int* delays, int64_t t, int32_t* out) {
+  if (K < 1 || !out || t < 0) return fail(DDS_EINVAL, "dds_schedule: bad arguments");
+  std::vector<int> d;
+  int rc = check_delays(K, delays, d);
+  if (rc) return rc;
+  for (int k0 = 0; k0 < K; ++k0) {
+    int32_t* o = out + (size_t)k0 * DDS_SCHED_INTS;
+    const int R = 2 * d[k0] + 1;
+    const int64_t f = t - k0, b = t - k0 - 2 * d[k0];
+    o[0] = (int32_t)f;
+    o[1] = (int32_t)b;
+    o[2] = R;
+    o[3] = (int32_t)(t % R);
+    o[4] = (int32_t)(((t - 2 * d[k0]) % R + R) % R);
+    if (k0 < K - 1) {
+      const int lag = 2 * (d[k0] - d[k0 + 1]) - 1;
+      o[5] = (int32_t)(((t - lag) % (lag + 1) + (lag + 1)) % (lag + 1));
+    } else {
+      o[5] = -1;
+    }
+    if (k0 > 0) {
+      const int lag = 2 * (d[k0 - 1] - d[k0]) - 1;
+      o[6] = (int32_t)(t % (lag + 1));
+    } else {
+      o[6] = -1;
+    }
+    o[7] = (k0 == K - 1 && f >= 0) ? (int32_t)(f % (K + 2 * d[K - 1])) : -1;
+  }
+  return DDS_OK;
+}
+
+int dds_arena_bytes(const dds_spec* spec, int K, int W, const int* delays, size_t* bytes) {
+  if (!bytes) return fail(DDS_EINVAL, "null bytes");
+  dds_ctx c;
+  int rc = build(c, spec, K, W, delays);
+  if (rc) return rc;
+  Arena A;
+  A.dry = true;
+  rc = layout(c, *spec, A);
+  if (rc) return rc;
+  *bytes = align_up(A.used, 256);
+  return DDS_OK;
+}
+
+int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* arena, size_t arena_bytes, dds_ctx** out) {
+  if (!out) return fail(DDS_EINVAL, "null out");
+  *out = nullptr;
+  if (!arena || ((uintptr_t)arena & 255)) return fail(DDS_EINVAL, "arena must be a 256-byte aligned device pointer");
+  dds_ctx* c = new dds_ctx();
+  int rc = build(*c, spec, K, W, delays);
+  if (rc) { delete c; return rc; }
+  Arena dry;
+  layout(*c, *spec, dry);
+  if (align_up(dry.used, 256) > arena_bytes) {
+    size_t need = align_up(dry.used, 256);
+    delete c;
+    return fail(DDS_ENOMEM, "arena has %zu bytes, %zu needed", arena_bytes, need);
+  }
+  Arena A;
+  A.dry = false;
+  A.base = (char*)arena;
+  A.size = arena_bytes;
+  // re-plan on a fresh context so that layout() sees untouched modules
+  delete c;
+  c = new dds_ctx();
+  rc = build(*c, spec, K, W, delays);
+  if (rc) { delete c; return rc; }
+  layout(*c, *spec, A);
+  c->arena_used = align_up(A.used, 256);
+  c->gemm_flops = count_flops(*c);
+  hipError_t e = hipMemset(arena, 0, c->arena_used);
+  if (e != hipSuccess) { delete c; return fail(DDS_EHIP, "hipMemset(arena) failed: %s", hipGetErrorString(e)); }
+  rc = upload_tables(*c);
+  if (rc) { delete c; return rc; }
+  e = hipEventCreateWithFlags(&c->fork, hipEventDisableTiming);
+  if (e != hipSuccess) { delete c; return fail(DDS_EHIP, "hipEventCreate failed: %s", hipGetErrorString(e)); }
+  if (K > 1) {
+    for (Module& m : c->mods) {
+      if (hipStreamCreateWithFlags(&m.stream, hipStreamNonBlocking) != hipSuccess ||
+          hipEventCreateWithFlags(&m.done, hipEventDisableTiming) != hipSuccess) {
+        dds_destroy(c);
+        return fail(DDS_EHIP, "stream/event creation failed");
+      }
+    }
+  }
+  HIP_TRY(hipDeviceSynchronize());
+  *out = c;
+  return DDS_OK;
+}
+
+int dds_destroy(dds_ctx* c) {
+  if (!c) return DDS_OK;
+  (void)hipDeviceSynchronize();
+  for (Module& m : c->mods) {
+    if (m.stream) (void)hipStreamDestroy(m.stream);
+    if (m.done) (void)hipEventDestroy(m.done);
+  }
+  if (c->fork) (void)hipEventDestroy(c->fork);
+  delete c;
+  return DDS_OK;
+}
+
+int64_t dds_param_count(const dds_ctx* c, int module) {
+  if (!c || module < 0 || module >= c->K) return fail(DDS_EINVAL, "dds_param_count: bad module");
+  return c->mods[module].canon_params;
+}
+
+int64_t dds_step_count(const dds_ctx* c) { return c ? c->t : (int64_t)fail(DDS_EINVAL, "null ctx"); }
+int64_t dds_launches_last_step(const dds_ctx* c) { return c ? c->launches : (int64_t)fail(DDS_EINVAL, "null ctx"); }
+double dds_gemm_flops_per_step(const dds_ctx* c) { return c ? c->gemm_flops : 0.0; }
+
+static int params_io(dds_ctx* c, int module, float* buf, size_t n_floats, void* stream, bool set) {
+  if (!c || module < 0 || module >= c->K || !buf) return fail(DDS_EINVAL, "bad ctx / module / pointer");
+  Module& m = c->mods[module];
+  if ((long long)n_floats != m.canon_params)
+    return fail(DDS_EINVAL, "module %d has %lld parameters, caller passed %zu", module, m.canon_params, n_floats);
+  hipStream_t s = (hipStream_t)stream;
+  size_t off = 0;
+  for (ParamLayer& L : m.layers) {
+    launch_param_permute(buf + off, m.master + L.off, L.Cout, L.Cin, L.RS, L.Cinpad, set ? 1 : 0, s);
+    off += (size_t)L.Cout * L.Cin * L.RS + L.Cout;
+  }
+  if (set) {
+    if (m.momentum) launch_fill_zero(m.momentum, (size_t)m.n_master * 4, s);
+    launch_recast(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, s);
+    for (int slot = 0; slot < m.R; ++slot) launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash, slot, s);
+  }
+  HIP_TRY(hipGetLastError());
+  return DDS_OK;
+}
+
+int dds_get_params(dds_ctx* c, int module, float* dst, size_t n, void* stream) { return params_io(c, module, dst, n, stream, false); }
+int dds_set_params(dds_ctx* c, int module, const float* src, size_t n, void* stream) {
+  if (c && c->t != 0) return fail(DDS_EINVAL, "dds_set_params is only valid before the first step");
+  return params_io(c, module, (float*)src, n, stream, true);
+}
+
+int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float lr, void* stream) {
+  if (!c || !x || !y) return fail(DDS_EINVAL, "dds_step: null argument");
+  for (int s = 0; s < c->W; ++s)
+    if (!x[s] || !y[s]) return fail(DDS_EINVAL, "dds_step: null batch pointer for replica %d", s);
+  hipStream_t us = (hipStream_t)stream;
+  const int64_t t = c->t;
+  const float step = std::isnan(lr) ? c->lr : lr;
+  c->launches = 0;
+
+  // ingest: caller batches -> module 0's ring slot t mod R_0 (layout + precision), labels -> queue
+  {
+    Module& m0 = c->mods[0];
+    IngestParams p{};
+    for (int s = 0; s < c->W; ++s) { p.x[s] = x[s]; p.y[s] = y[s]; }
+    p.dst = m0.ring + (size_t)(t % m0.R) * m0.slot_bytes + m0.tensors[0].ring_off;
+    p.labels = c->labels + (size_t)(t % c->label_depth) * c->N;
+    p.W = c->W; p.B = c->B; p.C = c->in_c; p.HW = c->in_h * c->in_w; p.Cpad = m0.tensors[0].Cpad;
+    launch_ingest(c->dt, p, us);
+    ++c->launches;
+  }
+  const bool multi = c->K > 1;
+  if (multi) HIP_TRY(hipEventRecord(c->fork, us));
+  for (int k0 = 0; k0 < c->K; ++k0) {
+    Module& m = c->mods[k0];
+    hipStream_t s = multi ? m.stream : us;
+    if (multi) HIP_TRY(hipStreamWaitEvent(s, c->fork, 0));
+    const int64_t f = t - k0, b = t - k0 - 2 * m.d;
+    const bool last = k0 == c->K - 1;
+    if (f >= 0) run_forward(*c, m, t, f, s);
+    if (last) {
+      const Node& ce = m.nodes.back();
+      const Tensor& lt = m.tensors[ce.in];
+      const int ldg = lt.Cpad;
+      if (f >= 0) {
+        const float* logits = (const float*)tptr(*c, m, ce.in, (int)(t % m.R), f);
+        const int32_t* lab = c->labels + (size_t)(f % c->label_depth) * c->N;
+        void* dl = (b == f) ? gptr(*c, m, ce.gin, t) : nullptr;
+        launch_softmax_ce(c->dt, logits, lab, dl, c->loss, c->W, c->B, c->classes, lt.Cpad, ldg, s);
+        ++c->launches;
+        c->have_loss = true;
+      }
+      if (b >= 0 && b != f) {
+        const int slot = (int)(((t - 2 * m.d) % m.R + m.R) % m.R);
+        const float* logits = (const float*)tptr(*c, m, ce.in, slot, b);
+        const int32_t* lab = c->labels + (size_t)(b % c->label_depth) * c->N;
+        launch_softmax_ce(c->dt, logits, lab, gptr(*c, m, ce.gin, t), nullptr, c->W, c->B, c->classes, lt.Cpad, ldg, s);
+        ++c->launches;
+      }
+    }
+    if (b >= 0) {
+      run_backward(*c, m, t, b, s);
+      launch_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->W, step, c->mu, s);
+      launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash, (int)((t + 1) % m.R), s);
+      c->launches += 2;
+    }
+    if (multi) {
+      HIP_TRY(hipEventRecord(m.done, s));
+      HIP_TRY(hipStreamWaitEvent(us, m.done, 0));
+    }
+  }
+  HIP_TRY(hipGetLastError());
+  c->t = t + 1;
+  return DDS_OK;
+}
+
+int dds_get_loss(dds_ctx* c, float* host_out, void* stream) {
+  if (!c || !host_out) return fail(DDS_EINVAL, "dds_get_loss: null argument");
+  if (!c->have_loss) return fail(DDS_EINVAL, "no loss yet: the last module has not forwarded a mini-batch");
+  float tmp[32];
+  HIP_TRY(hipMemcpyAsync(tmp, c->loss, sizeof(float) * c->W, hipMemcpyDeviceToHost, (hipStream_t)stream));
+  HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
+  double acc = 0;
+  for (int s = 0; s < c->W; ++s) acc += tmp[s];
+  *host_out = (float)(acc / c->W);
+  return DDS_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,115 @@
+// Launch interface between the host engine and the HIP kernels (gfx950 only).
+// Internal to the library: plain structs of device pointers and sizes.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dds {
+
+enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
+
+inline int dtype_size(int dt) { return dt == DT_F32 ? 4 : 2; }
+// channels per 16-byte chunk; every tensor's channel stride is a multiple of this
+inline int dtype_ce(int dt) { return dt == DT_F32 ? 4 : 8; }
+
+// Implicit-GEMM convolution / linear, forward or input-gradient (dgrad) form.
+//   y[m, n] = epilogue( sum_{tap, c} gather(x; m, tap)[c] * w[n, tap, c] )
+// forward : m = (img, ho, wo), gathers x at (ho*stride - pad + r, wo*stride - pad + s)
+// dgrad   : m = (img, h, w) of the conv input, x is the output gradient, gathers at
+//           ((h + pad - r)/stride, (w + pad - s)/stride) when divisible, w is the
+//           transposed weight snapshot [cin][tap][cout_padded]
+// epilogue: v = alpha * (acc + bias[n]); v += res[m, n]; relu; v = mask[m, n] > 0 ? v : 0
+struct ConvParams {
+  const void* x;
+  const void* w;
+  void* y;
+  const float* bias;  // fp32 [Nout] or null
+  const void* res;    // same layout as y (dtype T) or null
+  const void* mask;   // same layout as y (dtype T) or null
+  int Nimg, H, W, Cx; // gathered tensor: NHWC, channel stride Cx (= GEMM-K per tap)
+  int Ho, Wo;         // pixel grid of y; M = Nimg*Ho*Wo
+  int M;
+  int Nout;           // valid rows of w
+  int ldy;            // channel stride of y / res / mask
+  int R, S, stride, pad;
+  int Ktot;           // R*S*Cx
+  float alpha;
+  int relu;
+  int out_f32;        // y is fp32 regardless of T (logits)
+  int dgrad;
+};
+
+// Weight-gradient GEMM with split reduction:
+//   partial[z][m*NK + n] = alpha * sum_{p in split z} dy[p, m] * gather(x; p, n)
+//   partial[z][Mout*NK + m] = alpha * sum_p dy[p, m]                (bias gradient)
+// m = output channel, n = (tap, c), p = output pixel (img, ho, wo).
+struct WgradParams {
+  const void* dy;   // [P][ldy]
+  const void* x;    // [Nimg][H][W][Cx]
+  float* partial;   // [nsplit][Pl]
+  int Nimg, H, W, Cx, Ho, Wo;
+  int Mout;         // real output channels
+  int ldy;
+  int R, S, stride, pad;
+  int NK;           // R*S*Cx
+  int P;            // Nimg*Ho*Wo
+  int pix_per_split;
+  int nsplit;
+  long long Pl;     // floats between consecutive splits (>= Mout*NK + Mout)
+  float alpha;
+};
+
+struct IngestParams {
+  const float* x[32];
+  const int32_t* y[32];
+  void* dst;        // [W*B][H][W][Cpad] dtype T
+  int32_t* labels;  // [W*B]
+  int W, B, C, HW, Cpad;
+};
+
+// One entry per parameter tensor block of a module (weights followed by bias).
+struct UpdateDesc {
+  float* master;        // [n] fp32, internal layout
+  float* momentum;      // [n] or null
+  const float* partial; // [nsplit][n]
+  void* work;           // compute-precision copy [n] or null (fp32 path uses master)
+  void* stash;          // transposed snapshots [slot][Cin][RS][Coutpad] or null
+  long long stash_slot_elems;
+  long long n;          // Cout*RS*Cinpad + Cout
+  long long pstride;    // floats between consecutive splits of `partial` (n rounded up to 4)
+  int nsplit;
+  int Cout, RS, Cinpad, Cin, Coutpad;
+};
+
+void launch_conv(int dt, const ConvParams& p, hipStream_t s);
+void launch_wgrad(int dt, const WgradParams& p, hipStream_t s);
+// chooses the split count of the pixel reduction for a wgrad problem (multiple of W)
+int wgrad_choose_split(int dt, int Mout, int NK, int P, int W);
+
+void launch_ingest(int dt, const IngestParams& p, hipStream_t s);
+void launch_maxpool_fwd(int dt, const void* x, void* y, int N, int H, int W, int C, hipStream_t s);
+void launch_maxpool_bwd(int dt, const void* dy, const void* x, void* dx, int N, int H, int W, int C,
+                        int relu_mask, hipStream_t s);
+void launch_gap_fwd(int dt, const void* x, void* y, int N, int HW, int C, hipStream_t s);
+void launch_gap_bwd(int dt, const void* dy, const void* x, void* dx, int N, int HW, int C, int relu_mask,
+                    hipStream_t s);
+// logits fp32 [W*B][ldl]; dlogits dtype T [W*B][ldg] (may be null); loss [W] (may be null)
+void launch_softmax_ce(int dt, const float* logits, const int32_t* labels, void* dlogits, float* loss,
+                       int W, int B, int classes, int ldl, int ldg, hipStream_t s);
+// descs: device array of UpdateDesc; block_map: device array of (descriptor, block)
+// pairs, one per workgroup of 1024 elements.
+// update: g = (1/W) sum over splits, momentum, SGD on the fp32 master, recast into `work`.
+void launch_update(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks, int W,
+                   float lr, float mu, hipStream_t s);
+// work <- master
+void launch_recast(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks,
+                   hipStream_t s);
+// stash[slot] <- transpose(master); block_map enumerates blocks of Cin*RS*Coutpad elements
+void launch_stash(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks, int slot,
+                  hipStream_t s);
+// canonical [Cout][Cin][R][S] (+bias) <-> internal [Cout][RS][Cinpad] (+bias)
+void launch_param_permute(const float* canon, float* internal, int Cout, int Cin, int RS, int Cinpad,
+                          int to_internal, hipStream_t s);
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+
+}  // namespace dds

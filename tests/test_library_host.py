@@ -1,0 +1,104 @@
+"""Host-side checks of libdds that need no GPU: the library loads, exports every
+symbol the header declares, its integer schedule equals the oracle's closed forms,
+and spec validation / arena sizing behave."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2509_05679_amd as P
+from dds_inputs import workload, WORKLOAD_NAMES
+from dds_inputs.configs import tiny_mlp, tiny_resnet
+from oracle import fdg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "dds.h")).read()
+    declared = set(re.findall(r"\b(dds_[a-z_]+)\s*\(", header))
+    assert declared == set(P.EXPORTS)
+    for name in declared:
+        assert hasattr(P.lib, name), name
+
+
+@pytest.mark.parametrize("K", range(1, 9))
+def test_schedule_is_bit_exact_against_the_oracle(K):
+    for t in range(64):
+        got = P.dds_schedule(K, None, t)
+        for rec in fdg.schedule(t, K):
+            k0 = rec["k0"]
+            want = [rec["f"], rec["b"], rec["ring_depth"], rec["fwd_slot"], rec["bwd_slot"],
+                    rec["err_read"], rec["err_write"], rec["label_slot"]]
+            assert got[k0].tolist() == want, (K, t, k0)
+
+
+@pytest.mark.parametrize("K,d", [(3, [4, 2, 0]), (3, [3, 1, 0]), (4, [5, 4, 2, 1]), (2, [3, 1])])
+def test_schedule_with_custom_delays(K, d):
+    for t in range(40):
+        got = P.dds_schedule(K, d, t)
+        for rec in fdg.schedule(t, K, d):
+            k0 = rec["k0"]
+            want = [rec["f"], rec["b"], rec["ring_depth"], rec["fwd_slot"], rec["bwd_slot"],
+                    rec["err_read"], rec["err_write"], rec["label_slot"]]
+            assert got[k0].tolist() == want
+
+
+def test_schedule_rejects_acausal_delays():
+    with pytest.raises(P.DdsError) as e:
+        P.dds_schedule(3, [1, 1, 0], 0)
+    assert e.value.code == P.DDS_EINVAL
+    with pytest.raises(P.DdsError):
+        P.dds_schedule(2, [1, -1], 0)
+
+
+@pytest.mark.parametrize("name", WORKLOAD_NAMES)
+def test_arena_sizing_of_the_benchmark_configs(name):
+    wl = workload(name)
+    n = P.dds_arena_bytes(P.Spec.from_workload(wl), wl.K, wl.W)
+    assert 0 < n < 200 * 2 ** 30
+    half = workload(name, B=wl.B // 2)
+    assert P.dds_arena_bytes(P.Spec.from_workload(half), wl.K, wl.W) < n
+
+
+def _spec(ops, bounds, in_shape=(3, 8, 8), precision="f32"):
+    return P.Spec(ops, bounds, in_shape, 10, 4, precision, 0.1, 0.0)
+
+
+def test_spec_validation_errors():
+    good = tiny_resnet(K=2)
+    P.dds_arena_bytes(P.Spec.from_workload(good), 2, 2)
+    # channel mismatch
+    ops = [dict(op="conv", cin=4, cout=8, k=3, stride=1, pad=1), dict(op="relu"), dict(op="gap"),
+           dict(op="linear", cin=8, cout=10), dict(op="softmax_ce")]
+    with pytest.raises(P.DdsError) as e:
+        P.dds_arena_bytes(_spec(ops, [0, 5]), 1, 1)
+    assert e.value.code == P.DDS_EINVAL
+    # missing loss
+    ops2 = [dict(op="conv", cin=3, cout=8, k=3, stride=1, pad=1), dict(op="relu")]
+    with pytest.raises(P.DdsError):
+        P.dds_arena_bytes(_spec(ops2, [0, 2]), 1, 1)
+    # linear on a spatial tensor is not covered
+    ops3 = [dict(op="linear", cin=3, cout=10), dict(op="softmax_ce")]
+    with pytest.raises(P.DdsError) as e:
+        P.dds_arena_bytes(_spec(ops3, [0, 2]), 1, 1)
+    assert e.value.code == P.DDS_EUNSUPPORTED
+    # module boundary inside a residual block
+    wl = tiny_resnet(K=2)
+    with pytest.raises(P.DdsError):
+        P.dds_arena_bytes(P.Spec(wl.ops, [0, 4, len(wl.ops)], wl.in_shape, 10, 4, "f32", 0.1, 0.0), 2, 1)
+    # W out of range, bad bounds
+    with pytest.raises(P.DdsError):
+        P.dds_arena_bytes(P.Spec.from_workload(good), 2, 33)
+    with pytest.raises(P.DdsError):
+        P.dds_arena_bytes(P.Spec(good.ops, [0, 3, 3], good.in_shape, 10, 4, "f32", 0.1, 0.0), 2, 1)
+
+
+def test_no_gpu_means_a_loud_failure_not_a_fallback():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    wl = tiny_mlp()
+    with pytest.raises(RuntimeError):
+        P.Trainer(P.Spec.from_workload(wl), wl.W)

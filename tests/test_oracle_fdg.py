@@ -81,7 +81,7 @@ def test_ring_and_mailbox_slots_never_clobber_live_data(K, d):
     labels = {}
     for t in range(80):
         sch = fdg.schedule(t, K, d)
-        labels[t % K] = t
+        labels[t % (K + 2 * d[K - 1])] = t
         # reads happen against the state left by earlier iterations (plus own forward)
         for rec in sch:
             k0 = rec["k0"]
