@@ -42,6 +42,10 @@ template <> __device__ __forceinline__ void mfma16B<float>(const uint4& a, const
   c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
 }
 
+__device__ __forceinline__ uint4 keep_if(bool ok, const uint4& v) {
+  return make_uint4(ok ? v.x : 0u, ok ? v.y : 0u, ok ? v.z : 0u, ok ? v.w : 0u);
+}
+
 // One BKB-byte-deep step of a WM x WN wave tile. As / Bs point at the wave's first row.
 template <typename T, int WM, int WN, int BKB>
 __device__ __forceinline__ void mma_step(const char* As, const char* Bs, int lane, f32x16_t (&acc)[WM / 32][WN / 32]) {
@@ -61,9 +65,121 @@ __device__ __forceinline__ void mma_step(const char* As, const char* Bs, int lan
   }
 }
 
+// Four consecutive output channels of one pixel: v = alpha*(acc+bias) (+res) (relu) (mask),
+// moved with one 8-byte (bf16) or 16-byte (fp32) access per operand. n is a multiple of 4.
+template <typename T> __device__ __forceinline__ void load4(const void* p, size_t i, float* v);
+template <> __device__ __forceinline__ void load4<float>(const void* p, size_t i, float* v) {
+  const float4 t = *(const float4*)((const float*)p + i);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+template <> __device__ __forceinline__ void load4<bf16_t>(const void* p, size_t i, float* v) {
+  const uint2 t = *(const uint2*)((const uint16_t*)p + i);
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+template <typename T> __device__ __forceinline__ void store4(void* p, size_t i, const float* v);
+template <> __device__ __forceinline__ void store4<float>(void* p, size_t i, const float* v) {
+  *(float4*)((float*)p + i) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <> __device__ __forceinline__ void store4<bf16_t>(void* p, size_t i, const float* v) {
+  uint2 t;
+  t.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+  t.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+  *(uint2*)((uint16_t*)p + i) = t;
+}
+
+// Epilogue of one 32-pixel tile column of a wave: this lane owns pixel `pix` and, for each
+// of the NJ channel tiles, four groups of 4 consecutive channels starting at
+// nb + 32*j + 8*g. All residual / mask reads are issued up front from clamped addresses
+// (no branch around a load, so none of them is waited for one by one), then
+// v = alpha*(acc+bias) (+res) (relu) (mask) is formed and stored with predicated vector stores.
+template <typename T> struct Raw4;
+template <> struct Raw4<float> { typedef uint4 type; };
+template <> struct Raw4<bf16_t> { typedef uint2 type; };
+__device__ __forceinline__ void unpack4(const uint4& t, float* v) {
+  v[0] = __uint_as_float(t.x); v[1] = __uint_as_float(t.y); v[2] = __uint_as_float(t.z); v[3] = __uint_as_float(t.w);
+}
+__device__ __forceinline__ void unpack4(const uint2& t, float* v) {
+  v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+  v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+
+// bias values of this lane's channel groups (zero past Nout), read once per kernel
+template <int NJ>
+__device__ __forceinline__ void load_bias_groups(const ConvParams& p, int nb, float (&bias)[NJ][4][4]) {
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = nb + 32 * j + 8 * g + q;
+        float b = 0.f;
+        if (p.bias) b = p.bias[n < p.Nout ? n : 0];
+        bias[j][g][q] = n < p.Nout ? b : 0.f;
+      }
+}
+
+template <typename T, int NJ, int NI>
+__device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_t (&acc)[NJ][NI], int i, bool valid,
+                                              size_t pix, int nb, const float (&bias)[NJ][4][4]) {
+  typedef typename Raw4<T>::type raw_t;
+  size_t o[NJ][4];
+  bool ok[NJ][4];
+  raw_t r[NJ][4], mk[NJ][4];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int n = nb + 32 * j + 8 * g;
+      ok[j][g] = valid && n < p.ldy;
+      o[j][g] = ok[j][g] ? pix * p.ldy + n : 0;
+    }
+  if (p.res) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) r[j][g] = *(const raw_t*)((const T*)p.res + o[j][g]);
+  }
+  if (p.mask) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) mk[j][g] = *(const raw_t*)((const T*)p.mask + o[j][g]);
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      float v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = p.alpha * (acc[j][i][4 * g + q] + bias[j][g][q]);
+      if (p.res) {
+        float t[4];
+        unpack4(r[j][g], t);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] += t[q];
+      }
+      if (p.relu) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = v[q] > 0.f ? v[q] : 0.f;
+      }
+      if (p.mask) {
+        float t[4];
+        unpack4(mk[j][g], t);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = t[q] > 0.f ? v[q] : 0.f;
+      }
+      if (ok[j][g]) {
+        if (p.out_f32) store4<float>(p.y, o[j][g], v);
+        else store4<T>(p.y, o[j][g], v);
+      }
+    }
+}
+
 // ------------------------------------------------------------------ forward / dgrad
 template <typename T, int BM, int BN, int WM, int WN, int BKB, bool DGRAD>
-__global__ __launch_bounds__(256) void conv_gemm_kernel(ConvParams p) {
+__global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p) {
   constexpr int ES = sizeof(T);
   constexpr int CE = 16 / ES;     // elements per 16-byte chunk
   constexpr int BKE = BKB / ES;   // k elements per tile
@@ -149,13 +265,13 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(ConvParams p) {
     for (int i = 0; i < BP; ++i) *(uint4*)(Bs + (rbase + i * ROWS) * LDK + chunk * 16) = rb[i];
   };
 
-  f32x16_t acc[WM / 32][WN / 32];
+  f32x16_t acc[WN / 32][WM / 32];
 #pragma unroll
-  for (int i = 0; i < WM / 32; ++i)
+  for (int j = 0; j < WN / 32; ++j)
 #pragma unroll
-    for (int j = 0; j < WN / 32; ++j)
+    for (int i = 0; i < WM / 32; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
   const int nk = (p.Ktot + BKE - 1) / BKE;
   load_global();
@@ -166,33 +282,236 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(ConvParams p) {
     if (kt + 1 < nk) load_global();
     const char* As = smem + buf * (BM + BN) * LDK + wave_m * WM * LDK;
     const char* Bs = smem + buf * (BM + BN) * LDK + BM * LDK + wave_n * WN * LDK;
-    mma_step<T, WM, WN, BKB>(As, Bs, lane, acc);
+    // weights are the MFMA A operand so that a lane ends up with 4 consecutive output
+    // channels of one pixel (one vector access per operand in the epilogue)
+    mma_step<T, WN, WM, BKB>(Bs, As, lane, acc);
     if (kt + 1 < nk) store_lds(buf ^ 1);
     __syncthreads();
   }
 
-  // epilogue: lane holds column n = lane%32 and rows 8*(e/4) + 4*(lane/32) + e%4 of each 32x32 tile
+  // lane holds pixel m = lane%32 and channels 8*g + 4*(lane/32) + (0..3), g = 0..3, of each 32x32 tile
+  const int nb = n0 + wave_n * WN + 4 * (lane >> 5);
+  float bias[WN / 32][4][4];
+  load_bias_groups<WN / 32>(p, nb, bias);
 #pragma unroll
-  for (int j = 0; j < WN / 32; ++j) {
-    const int n = n0 + wave_n * WN + j * 32 + (lane & 31);
-    if (n >= p.ldy) continue;
-    const float bias = (p.bias != nullptr && n < p.Nout) ? p.bias[n] : 0.f;
-#pragma unroll
-    for (int i = 0; i < WM / 32; ++i) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wave_m * WM + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        if (m >= p.M) continue;
-        const size_t o = (size_t)m * p.ldy + n;
-        float v = p.alpha * (acc[i][j][e] + bias);
-        if (p.res) v += load_elem<T>(p.res, o);
-        if (p.relu) v = v > 0.f ? v : 0.f;
-        if (p.mask) v = load_elem<T>(p.mask, o) > 0.f ? v : 0.f;
-        if (p.out_f32) ((float*)p.y)[o] = v;
-        else store_elem<T>(p.y, o, v);
-      }
-    }
+  for (int i = 0; i < WM / 32; ++i) {
+    const int m = m0 + wave_m * WM + i * 32 + (lane & 31);
+    epilogue_tile<T, WN / 32, WM / 32>(p, acc, i, m < p.M, (size_t)m, nb, bias);
   }
+}
+
+// ------------------------------------------------------------------ 3x3 stride-1 forward / dgrad with an LDS halo patch
+// The workgroup owns 256 output pixels (a TH x TW rectangle of one image, or IMGS whole
+// small images) and BN output channels. Per 128-byte channel chunk the input patch
+// including its one-pixel halo is staged in LDS ONCE and all nine taps read their A
+// operands from it at shifted addresses, so activations cross the L2 about 1.3x instead
+// of 9x; zero padding is materialised in the patch, not tested in the inner loop. The
+// weight tile of each (tap, chunk) streams through a double buffer.
+struct HaloGeom {
+  int tw_log, th_log;      // log2 of the tile width / height in pixels
+  int tiles_w, tiles_h;    // tiles per image
+  int imgs;                // images per tile
+  int PW, PP;              // patch row pitch (TW+2) and pixels per image patch ((TH+2)*(TW+2))
+  int patch_pix;           // imgs * PP
+  int patch_bytes;         // patch_pix * 144 rounded to 256
+  int flip;                // dgrad: tap (r,s) reads the patch at (2-r, 2-s)
+};
+
+template <typename T, int BN, int WM, int WN, int BKB>
+__global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(ConvParams p, HaloGeom g) {
+  constexpr int ES = sizeof(T);
+  constexpr int BM = 256, LDK = BKB + 16;
+  constexpr int CPR = BKB / 16;          // 16-byte columns per LDS row
+  constexpr int WP = BN * CPR / 256;     // 16-byte weight chunks per thread per (tap, chunk)
+  constexpr int PSTEP = 256 / CPR;       // patch pixels covered by one pass of all threads
+  static_assert((BM / WM) * (BN / WN) == 4, "four waves");
+  extern __shared__ __align__(16) char smem[];
+  char* patch = smem;
+  char* wbuf = smem + g.patch_bytes;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave % (BM / WM), wave_n = wave / (BM / WM);
+  const int tiles_per_img = g.tiles_w * g.tiles_h;
+  const int grp = blockIdx.x / tiles_per_img, tin = blockIdx.x - grp * tiles_per_img;
+  const int th_idx = tin / g.tiles_w, tw_idx = tin - th_idx * g.tiles_w;
+  const int img0 = grp * g.imgs, h0 = th_idx << g.th_log, w0 = tw_idx << g.tw_log;
+  const int n0 = blockIdx.y * BN;
+  const int TWm = (1 << g.tw_log) - 1, THm = (1 << g.th_log) - 1;
+  const int PH = (1 << g.th_log) + 2;
+
+  int abase[WM / 32], bbase[WN / 32];
+#pragma unroll
+  for (int i = 0; i < WM / 32; ++i) {
+    const int m = wave_m * WM + i * 32 + (lane & 31);
+    const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
+    abase[i] = (im * g.PP + y * g.PW + x) * LDK + (lane >> 5) * 16;
+  }
+#pragma unroll
+  for (int j = 0; j < WN / 32; ++j) bbase[j] = (wave_n * WN + j * 32 + (lane & 31)) * LDK + (lane >> 5) * 16;
+
+  // weight stream: iteration it = chunk*9 + tap
+  const int nchunks = (p.Cx * ES) / BKB;
+  const int niter = nchunks * 9;
+  const char* wrow[WP];
+  bool wok[WP];
+#pragma unroll
+  for (int q = 0; q < WP; ++q) {
+    const int id = tid + q * 256, row = id / CPR, c16 = id % CPR;
+    wok[q] = n0 + row < p.Nout;
+    wrow[q] = (const char*)p.w + (size_t)(wok[q] ? n0 + row : 0) * 9 * p.Cx * ES + c16 * 16;
+  }
+  uint4 wregA[WP], wregB[WP];  // two named register sets (no dynamic indexing: stays in VGPRs)
+  // Loads are unconditional (rows past the end are clamped to row 0 and zeroed when parked
+  // in LDS): with no branch around a load the compiler can count the requests in flight and
+  // wait for exactly the older ones, which is what lets a request span two compute phases.
+  auto load_w = [&](int it, uint4 (&dst)[WP]) {
+    const int chunk = it / 9, tap = it - chunk * 9;
+    const size_t off = (size_t)tap * p.Cx * ES + (size_t)chunk * BKB;
+#pragma unroll
+    for (int q = 0; q < WP; ++q) dst[q] = *(const uint4*)(wrow[q] + off);
+  };
+  auto store_w = [&](int slot, const uint4 (&src)[WP]) {
+    char* wb = wbuf + slot * BN * LDK;
+#pragma unroll
+    for (int q = 0; q < WP; ++q) {
+      const int id = tid + q * 256;
+      *(uint4*)(wb + (id / CPR) * LDK + (id % CPR) * 16) = keep_if(wok[q], src[q]);
+    }
+  };
+  // patch loader: this thread owns 16-byte column c16 = tid%CPR of patch pixels tid/CPR + PSTEP*k
+  auto load_patch = [&](int chunk) {
+    const int c16 = tid % CPR;
+    int pp = tid / CPR;
+    int im = pp / g.PP, rem = pp - im * g.PP;
+    int yy = rem / g.PW, xx = rem - yy * g.PW;
+    const char* src = (const char*)p.x + (size_t)chunk * BKB + c16 * 16;
+    for (; pp < g.patch_pix; pp += 4 * PSTEP) {
+      uint4 v[4];
+      int pq[4];
+      bool ok[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        pq[u] = pp + u * PSTEP;
+        const int gi = img0 + im, gh = h0 + yy - 1, gw = w0 + xx - 1;
+        ok[u] = pq[u] < g.patch_pix && gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W;
+        const size_t o = ok[u] ? ((((size_t)gi * p.H + gh) * p.W + gw) * p.Cx) * ES : 0;
+        v[u] = *(const uint4*)(src + o);
+        xx += PSTEP;
+        while (xx >= g.PW) { xx -= g.PW; ++yy; }
+        while (yy >= PH) { yy -= PH; ++im; }
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (pq[u] < g.patch_pix) *(uint4*)(patch + pq[u] * LDK + c16 * 16) = keep_if(ok[u], v[u]);
+    }
+  };
+
+  f32x16_t acc[WN / 32][WM / 32];
+#pragma unroll
+  for (int j = 0; j < WN / 32; ++j)
+#pragma unroll
+    for (int i = 0; i < WM / 32; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+  // One pipeline stage. Weight tile it+2 is requested before the MFMAs of tile it and tile
+  // it+1 (requested a whole stage earlier, in `nxt`) is parked in LDS after them, so a
+  // request has two compute phases to land. Two LDS slots: it+1 goes where it-1 was.
+  auto stage = [&](int it, uint4 (&nxt)[WP], uint4 (&fre)[WP]) {
+    const int chunk = it / 9, tap = it - chunk * 9;
+    if (tap == 0) {
+      load_patch(chunk);  // the barrier that ended the previous stage freed the patch
+      __syncthreads();
+    }
+    if (it + 2 < niter) load_w(it + 2, fre);
+    const int r = tap / 3, sx = tap - r * 3;
+    const int tapoff = ((g.flip ? 2 - r : r) * g.PW + (g.flip ? 2 - sx : sx)) * LDK;
+    const char* wb = wbuf + (it & 1) * BN * LDK;
+#pragma unroll
+    for (int ks = 0; ks < BKB / 32; ++ks) {
+      uint4 a[WM / 32], b[WN / 32];
+#pragma unroll
+      for (int i = 0; i < WM / 32; ++i) a[i] = *(const uint4*)(patch + abase[i] + tapoff + ks * 32);
+#pragma unroll
+      for (int j = 0; j < WN / 32; ++j) b[j] = *(const uint4*)(wb + bbase[j] + ks * 32);
+#pragma unroll
+      for (int j = 0; j < WN / 32; ++j)
+#pragma unroll
+        for (int i = 0; i < WM / 32; ++i) mfma16B<T>(b[j], a[i], acc[j][i]);
+    }
+    if (it + 1 < niter) store_w((it + 1) & 1, nxt);
+    __syncthreads();  // tile it+1 visible; tile it and (at a chunk end) the patch are free
+  };
+
+  load_w(0, wregA);
+  store_w(0, wregA);  // made visible by the barrier after the first patch load
+  if (niter > 1) load_w(1, wregB);
+  for (int it = 0; it < niter; it += 2) {
+    stage(it, wregB, wregA);
+    if (it + 1 < niter) stage(it + 1, wregA, wregB);
+  }
+
+  const int nb = n0 + wave_n * WN + 4 * (lane >> 5);
+  float bias[WN / 32][4][4];
+  load_bias_groups<WN / 32>(p, nb, bias);
+#pragma unroll
+  for (int i = 0; i < WM / 32; ++i) {
+    const int m = wave_m * WM + i * 32 + (lane & 31);
+    const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
+    const int gi = img0 + im;
+    const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
+    epilogue_tile<T, WN / 32, WM / 32>(p, acc, i, gi < p.Nimg, pix, nb, bias);
+  }
+}
+
+inline int ilog2_exact(int v) {
+  int l = 0;
+  while ((1 << l) < v) ++l;
+  return (1 << l) == v ? l : -1;
+}
+
+// Fills g and returns true when the halo kernel covers this problem.
+template <typename T>
+bool halo_geometry(const ConvParams& p, HaloGeom& g) {
+  constexpr int CK = 64 / sizeof(T);
+  if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1 || p.H != p.Ho || p.W != p.Wo) return false;
+  if (p.Cx % CK != 0 || p.out_f32) return false;
+  const int lw = ilog2_exact(p.W), lh = ilog2_exact(p.H);
+  if (lw < 1 || lh < 1 || p.W > 32) return false;
+  int TW = p.W, TH, imgs;
+  if (p.H * p.W >= 256) {
+    TH = 256 / TW;
+    imgs = 1;
+    if (TH > p.H || p.H % TH) return false;
+  } else {
+    TH = p.H;
+    imgs = 256 / (p.H * p.W);
+  }
+  g.tw_log = ilog2_exact(TW);
+  g.th_log = ilog2_exact(TH);
+  g.tiles_w = p.W / TW;
+  g.tiles_h = p.H / TH;
+  g.imgs = imgs;
+  g.PW = TW + 2;
+  g.PP = (TH + 2) * (TW + 2);
+  g.patch_pix = imgs * g.PP;
+  g.patch_bytes = (g.patch_pix * 144 + 255) / 256 * 256;
+  g.flip = p.dgrad;
+  return true;
+}
+
+template <typename T, int BN, int WM, int WN, int BKB>
+void launch_halo_inst(const ConvParams& p, HaloGeom g, hipStream_t s) {
+  static bool attr_set = false;
+  g.patch_bytes = (g.patch_pix * (BKB + 16) + 255) / 256 * 256;
+  const int smem = g.patch_bytes + 2 * BN * (BKB + 16);
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)conv3x3_halo_kernel<T, BN, WM, WN, BKB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_set = true;
+  }
+  const int groups = (p.Nimg + g.imgs - 1) / g.imgs;
+  dim3 grid(groups * g.tiles_w * g.tiles_h, (p.ldy + BN - 1) / BN);
+  conv3x3_halo_kernel<T, BN, WM, WN, BKB><<<grid, 256, smem, s>>>(p, g);
 }
 
 // ------------------------------------------------------------------ wgrad
@@ -223,7 +542,7 @@ template <> __device__ __forceinline__ uint4 one_chunk<float>() { return make_ui
 template <> __device__ __forceinline__ uint4 one_chunk<bf16_t>() { return make_uint4(0x3f80u, 0, 0, 0); }
 
 template <typename T, int BM, int BN, int WM, int WN>
-__global__ __launch_bounds__(256) void wgrad_gemm_kernel(WgradParams p) {
+__global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradParams p) {
   constexpr int ES = sizeof(T);
   constexpr int CE = 16 / ES;
   constexpr int BKB = 128;
@@ -363,9 +682,18 @@ __global__ __launch_bounds__(256) void wgrad_gemm_kernel(WgradParams p) {
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
+#ifndef HALO_BKB
+#define HALO_BKB 64
+#endif
 template <typename T>
 void launch_conv_t(const ConvParams& p, hipStream_t s) {
   constexpr int BKB = 64;
+  HaloGeom g;
+  if (halo_geometry<T>(p, g)) {
+    if (p.ldy <= 64) launch_halo_inst<T, 64, 64, 64, HALO_BKB>(p, g, s);
+    else launch_halo_inst<T, 128, 128, 64, HALO_BKB>(p, g, s);
+    return;
+  }
   if (p.ldy <= 64) {
     dim3 grid(cdiv(p.M, 256), cdiv(p.ldy, 64));
     if (p.dgrad) conv_gemm_kernel<T, 256, 64, 64, 64, BKB, true><<<grid, 256, 0, s>>>(p);
@@ -410,6 +738,7 @@ int wgrad_choose_split(int dt, int Mout, int NK, int P, int W) {
   int qmax = per_replica / (2 * bke);  // at least two k-tiles per split
   if (qmax < 1) qmax = 1;
   if (q > qmax) q = qmax;
+  if (q * W > 256) q = 256 / W;  // the update kernel walks the splits serially
   if (q < 1) q = 1;
   while (q > 1 && per_replica % q != 0) --q;  // splits never straddle replicas
   return W * q;

@@ -240,11 +240,28 @@ __global__ __launch_bounds__(256) void update_kernel(const UpdateDesc* descs, co
   const long long base = (long long)block_map[2 * blockIdx.x + 1] * 1024 + threadIdx.x * 4;
   if (base >= d.n) return;
   if (base + 4 <= d.n) {
-    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < d.nsplit; ++j) {
-      const float4 q = *(const float4*)(d.partial + (size_t)j * d.pstride + base);
-      g.x += q.x; g.y += q.y; g.z += q.z; g.w += q.w;
+    // fixed summation order (bit-reproducible): eight interleaved running sums keep
+    // eight loads in flight, then a fixed tree combines them
+    float4 a[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    int j = 0;
+    for (; j + 8 <= d.nsplit; j += 8) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const float4 q = *(const float4*)(d.partial + (size_t)(j + u) * d.pstride + base);
+        a[u].x += q.x; a[u].y += q.y; a[u].z += q.z; a[u].w += q.w;
+      }
     }
+    for (int u = 0; j < d.nsplit; ++j, ++u) {
+      const float4 q = *(const float4*)(d.partial + (size_t)j * d.pstride + base);
+      a[u].x += q.x; a[u].y += q.y; a[u].z += q.z; a[u].w += q.w;
+    }
+#pragma unroll
+    for (int w = 4; w > 0; w >>= 1)
+#pragma unroll
+      for (int u = 0; u < w; ++u) { a[u].x += a[u + w].x; a[u].y += a[u + w].y; a[u].z += a[u + w].z; a[u].w += a[u + w].w; }
+    float4 g = a[0];
     g.x *= invW; g.y *= invW; g.z *= invW; g.w *= invW;
     float4 w = *(const float4*)(d.master + base);
     if (d.momentum) {
