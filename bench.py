@@ -31,6 +31,19 @@ def hip_event_timer():
     return hip
 
 
+def read_traffic(workload_name):
+    """HBM bytes per GEMM launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs, if the
+    summary for this workload has been recorded under profiles/ (else None)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 3 and f[0] == workload_name and f[1] == "gemm_bytes_per_launch":
+            return float(f[2])
+    return None
+
+
 def cpu_baseline(wl, seconds_budget=20.0):
     """The oracle as it stands on a bounded sample: same K / W / delays / layers with a
     reduced per-replica batch, timed over steady-state iterations."""
@@ -118,12 +131,24 @@ def main():
     flops = tr.dds_gemm_flops_per_step()
     launches = tr.dds_launches_last_step()
 
-    # roofline of the dominant kernel class (the MFMA implicit-GEMM kernels): algorithmic
-    # FLOPs of all conv/linear forward+dgrad+wgrad launches of a step over the step time
-    # measured here with HIP events. The step also contains the bandwidth-bound kernels, so
-    # this is a lower bound on the GEMM kernels' own rate (per-kernel times: profiles/).
-    achieved = flops / (ms_per_step * 1e-3) / 1e12
+    # Roofline of the dominant kernel class: the MFMA implicit-GEMM kernels (forward, dgrad
+    # and wgrad of every conv / linear layer). A second, untimed pass brackets each of those
+    # launches with HIP events on the stream it is launched on (dds_profile); achieved =
+    # algorithmic FLOPs (2*M*N*K per launch) / summed launch durations. Modules run on
+    # concurrent streams, so a launch's duration includes the time it shares the chip.
+    tr.dds_profile(True)
+    for t in range(max(4, min(args.steps, 10))):
+        tr.dds_step(xs[t % pool], ys[t % pool])
+    prof = tr.dds_profile_read()
+    tr.dds_profile(False)
+    gemm_ms = sum(v[0] for v in prof.values())
+    gemm_flops = sum(v[2] for v in prof.values())
+    gemm_launches = sum(v[1] for v in prof.values())
+    achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     peak = PEAK[wl.precision]
+    per_class = {k: {"avg_us": 1e3 * v[0] / max(v[1], 1), "TFLOP/s": v[2] / max(v[0], 1e-9) / 1e9,
+                     "launches_per_step": v[1] / max(4, min(args.steps, 10))} for k, v in prof.items()}
+    traffic = read_traffic(wl.name)
     out = {
         "metric": "training samples/sec on 1 MI355X per decoupled step",
         "value": samples / (ms_per_step * 1e-3),
@@ -141,8 +166,10 @@ def main():
                    "launches_per_step": launches, "wall_ms_per_step": wall * 1e3 / args.steps,
                    "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": None,
-                     "note": "conv/linear fwd+dgrad+wgrad algorithmic FLOPs per step over the whole step time"},
+                     "frac": achieved / peak, "traffic": traffic,
+                     "kernel": "conv/linear implicit-GEMM (forward + dgrad + wgrad launches)",
+                     "avg_launch_us": 1e3 * gemm_ms / max(gemm_launches, 1), "per_class": per_class,
+                     "whole_step_TFLOP/s": flops / (ms_per_step * 1e-3) / 1e12},
     }
     tr.close()
     if not args.no_cpu_baseline:

@@ -140,6 +140,15 @@ int64_t dds_step_count(const dds_ctx* ctx);
 int64_t dds_launches_last_step(const dds_ctx* ctx);
 double dds_gemm_flops_per_step(const dds_ctx* ctx);
 
+/* Per-launch timing of the MFMA kernels for the benchmark's roofline record. While
+ * enabled every conv/linear forward, dgrad and wgrad launch is bracketed by HIP events on
+ * the stream it is launched on and dds_step synchronises at its end (do not time
+ * throughput in this mode). dds_profile(ctx, 1) also clears the totals.
+ * dds_profile_read fills 9 doubles: for class 0 forward, 1 dgrad, 2 wgrad:
+ * summed milliseconds, number of launches, summed algorithmic FLOPs (2*M*N*K). */
+int dds_profile(dds_ctx* ctx, int enable);
+int dds_profile_read(const dds_ctx* ctx, double* out9);
+
 const char* dds_last_error(void);
 
 #ifdef __cplusplus

@@ -25,7 +25,8 @@ PRECISION = {"f32": 0, "bf16": 1}
 
 EXPORTS = ["dds_schedule", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
            "dds_get_params", "dds_set_params", "dds_step", "dds_get_loss", "dds_step_count",
-           "dds_launches_last_step", "dds_gemm_flops_per_step", "dds_last_error"]
+           "dds_launches_last_step", "dds_gemm_flops_per_step", "dds_profile", "dds_profile_read",
+           "dds_last_error"]
 
 
 class dds_layer(C.Structure):
@@ -68,6 +69,8 @@ def _load():
     lib.dds_launches_last_step.restype = C.c_int64
     lib.dds_gemm_flops_per_step.argtypes = [vp]
     lib.dds_gemm_flops_per_step.restype = C.c_double
+    lib.dds_profile.argtypes = [vp, C.c_int]
+    lib.dds_profile_read.argtypes = [vp, C.POINTER(C.c_double)]
     lib.dds_last_error.restype = C.c_char_p
     return lib
 
@@ -187,6 +190,16 @@ class Trainer:
 
     def dds_gemm_flops_per_step(self) -> float:
         return float(lib.dds_gemm_flops_per_step(self.ctx))
+
+    def dds_profile(self, enable: bool):
+        _check(lib.dds_profile(self.ctx, 1 if enable else 0))
+
+    def dds_profile_read(self):
+        """{class: (ms, launches, flops)} for forward / dgrad / wgrad launches."""
+        out = (C.c_double * 9)()
+        _check(lib.dds_profile_read(self.ctx, out))
+        return {name: (out[3 * i], int(out[3 * i + 1]), out[3 * i + 2])
+                for i, name in enumerate(("forward", "dgrad", "wgrad"))}
 
     def close(self):
         if getattr(self, "ctx", None):

@@ -34,6 +34,12 @@ def build(verbose: bool = True) -> str:
     r = subprocess.run(link, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}")
+    # stand-alone 1 GiB copy kernel: calibrates the FETCH_SIZE / WRITE_SIZE counters (profiles/)
+    probe = [hipcc, "--offload-arch=gfx950", "-O2", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             os.path.join(CSRC, "copy_probe.hip"), "-o", os.path.join(HERE, "copy_probe")]
+    r = subprocess.run(probe, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"copy_probe build failed:\n{r.stdout}")
     return LIB
 
 

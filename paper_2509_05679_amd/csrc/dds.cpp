@@ -150,6 +150,13 @@ struct dds_ctx {
   int64_t launches = 0;
   double gemm_flops = 0.0;
   size_t arena_used = 0;
+  // optional per-launch timing of the MFMA kernels (events on the launching stream)
+  bool profiling = false;
+  struct ProfRec { int cls; double flops; hipEvent_t a, b; };
+  std::vector<ProfRec> prof_pending;
+  std::vector<hipEvent_t> prof_pool;
+  double prof_ms[3] = {0, 0, 0}, prof_flops[3] = {0, 0, 0};
+  long long prof_count[3] = {0, 0, 0};
 };
 
 namespace {
@@ -556,6 +563,24 @@ char* gptr(dds_ctx& c, Module& m, int gid, int64_t t) {
   return nullptr;
 }
 
+hipEvent_t prof_event(dds_ctx& c) {
+  if (!c.prof_pool.empty()) { hipEvent_t e = c.prof_pool.back(); c.prof_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  (void)hipEventCreate(&e);
+  return e;
+}
+
+// cls: 0 forward, 1 dgrad, 2 wgrad
+struct ProfScope {
+  dds_ctx& c; hipStream_t s; int cls; double flops; hipEvent_t a = nullptr;
+  ProfScope(dds_ctx& c_, hipStream_t s_, int cls_, double flops_) : c(c_), s(s_), cls(cls_), flops(flops_) {
+    if (c.profiling) { a = prof_event(c); (void)hipEventRecord(a, s); }
+  }
+  ~ProfScope() {
+    if (c.profiling) { hipEvent_t b = prof_event(c); (void)hipEventRecord(b, s); c.prof_pending.push_back({cls, flops, a, b}); }
+  }
+};
+
 void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
   const int slot = (int)(t % m.R);
   const int es = dtype_size(c.dt);
@@ -586,7 +611,10 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
         p.relu = nd.relu;
         p.out_f32 = nd.out_f32;
         p.dgrad = 0;
-        launch_conv(c.dt, p, s);
+        {
+          ProfScope ps(c, s, 0, 2.0 * p.M * L.Cout * L.Cin * L.RS);
+          launch_conv(c.dt, p, s);
+        }
         break;
       }
       case N_MAXPOOL:
@@ -629,7 +657,10 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
         w.pix_per_split = w.P / L.nsplit;
         w.Pl = L.pstride;
         w.alpha = nd.alpha;
-        launch_wgrad(c.dt, w, s);
+        {
+          ProfScope ps(c, s, 2, 2.0 * w.P * L.Cout * L.Cin * L.RS);
+          launch_wgrad(c.dt, w, s);
+        }
         ++c.launches;
         if (nd.gin != G_NONE) {
           ConvParams p{};
@@ -650,7 +681,10 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
           p.relu = 0;
           p.out_f32 = 0;
           p.dgrad = 1;
-          launch_conv(c.dt, p, s);
+          {
+            ProfScope ps(c, s, 1, 2.0 * w.P * L.Cout * L.Cin * L.RS);
+            launch_conv(c.dt, p, s);
+          }
           ++c.launches;
         }
         break;
@@ -805,6 +839,7 @@ int dds_destroy(dds_ctx* c) {
     if (m.done) (void)hipEventDestroy(m.done);
   }
   if (c->fork) (void)hipEventDestroy(c->fork);
+  for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
   delete c;
   return DDS_OK;
 }
@@ -906,6 +941,37 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
   }
   HIP_TRY(hipGetLastError());
   c->t = t + 1;
+  if (c->profiling) {  // harvest this step's event pairs (synchronises: profiling runs are not timed runs)
+    HIP_TRY(hipStreamSynchronize(us));
+    for (auto& r : c->prof_pending) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+        c->prof_ms[r.cls] += ms;
+        c->prof_flops[r.cls] += r.flops;
+        c->prof_count[r.cls] += 1;
+      }
+      c->prof_pool.push_back(r.a);
+      c->prof_pool.push_back(r.b);
+    }
+    c->prof_pending.clear();
+  }
+  return DDS_OK;
+}
+
+int dds_profile(dds_ctx* c, int enable) {
+  if (!c) return fail(DDS_EINVAL, "null ctx");
+  c->profiling = enable != 0;
+  for (int i = 0; i < 3; ++i) { c->prof_ms[i] = 0; c->prof_flops[i] = 0; c->prof_count[i] = 0; }
+  return DDS_OK;
+}
+
+int dds_profile_read(const dds_ctx* c, double* out9) {
+  if (!c || !out9) return fail(DDS_EINVAL, "null argument");
+  for (int i = 0; i < 3; ++i) {
+    out9[3 * i + 0] = c->prof_ms[i];
+    out9[3 * i + 1] = (double)c->prof_count[i];
+    out9[3 * i + 2] = c->prof_flops[i];
+  }
   return DDS_OK;
 }
 
