@@ -144,6 +144,7 @@ struct dds_ctx {
   int label_depth = 0;
   int32_t* labels = nullptr;  // [label_depth][N]
   float* loss = nullptr;      // [W]
+  char* zeros = nullptr;      // 256 zero bytes
   int64_t t = 0;
   bool have_loss = false;
   hipEvent_t fork = nullptr;
@@ -460,6 +461,7 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
   c.label_depth = c.K + 2 * c.d[c.K - 1];
   c.labels = (int32_t*)A.take(sizeof(int32_t) * c.N * c.label_depth);
   c.loss = (float*)A.take(sizeof(float) * c.W);
+  c.zeros = A.take(256);
   (void)sp;
   return DDS_OK;
 }
@@ -600,6 +602,7 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
         p.bias = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
         p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
         p.mask = nullptr;
+        p.zeros = c.zeros;
         p.Nimg = c.N; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
         p.Ho = to.H; p.Wo = to.W;
         p.M = c.N * to.H * to.W;
@@ -647,6 +650,7 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
         w.dy = gout;
         w.x = x;
         w.partial = L.partial;
+        w.zeros = c.zeros;
         w.Nimg = c.N; w.H = ti.H; w.W = ti.W; w.Cx = ti.Cpad; w.Ho = to.H; w.Wo = to.W;
         w.Mout = L.Cout;
         w.ldy = ldg;
@@ -670,6 +674,7 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
           p.bias = nullptr;
           p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
           p.mask = nd.mask_in ? x : nullptr;
+          p.zeros = c.zeros;
           p.Nimg = c.N; p.H = to.H; p.W = to.W; p.Cx = ldg;
           p.Ho = ti.H; p.Wo = ti.W;
           p.M = c.N * ti.H * ti.W;

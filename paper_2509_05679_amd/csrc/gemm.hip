@@ -464,6 +464,196 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(ConvParams p, Halo
   }
 }
 
+// ------------------------------------------------------------------ 3x3 stride-1 forward / dgrad, asynchronous LDS fills
+// Same tiling as the halo kernel above, but every operand byte travels global -> LDS
+// with global_load_lds_dwordx4 (no staging registers, lane L of a wave fills bytes
+// [16L, 16L+16) of a 1 KiB LDS block), issued two pipeline stages (tap, channel chunk)
+// ahead of its use: weight tiles rotate through three LDS slots and the next channel
+// chunk's patch is fetched in slices spread over taps 0..6 of the current one. The
+// compiler does not model these copies, so their completion is counted by hand: loads
+// retire in order, every stage issues a fixed number per lane, and each stage waits
+// until only the younger ones are outstanding, then crosses one workgroup barrier.
+// LDS rows are 128 unpadded bytes; the 16-byte column c of row r lives at column
+// c ^ (r & 7), which keeps eight consecutive rows on distinct banks for the MFMA
+// fragment reads; the swizzle is applied by choosing which global column a lane fetches.
+#define DDS_LDS_AS __attribute__((address_space(3)))
+__device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base_uniform) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+struct DmaGeom {
+  HaloGeom h;
+  int patch_rows;   // patch pixels rounded up to 8 (one wave fill = 8 rows)
+  int tab_bytes;    // pixel-offset table, rounded to 1 KiB
+};
+
+template <typename T, int BM, int BN, int WM, int WN, int PS>
+__global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGeom dg) {
+  constexpr int ES = sizeof(T);
+  constexpr int WL = BN / 32;  // weight fills per lane per stage
+  constexpr int NI = WM / 32, NJ = WN / 32;
+  static_assert((BM / WM) * (BN / WN) == 4, "four waves");
+  extern __shared__ __align__(16) char smem[];
+  const HaloGeom& g = dg.h;
+  const int prow = dg.patch_rows;
+  const int pbuf_bytes = prow * 128;
+  int* tab = (int*)smem;
+  char* pbuf = smem + dg.tab_bytes;
+  char* wring = pbuf + (PS > 0 ? 2 : 1) * pbuf_bytes;
+  const uint32_t lds0 = (uint32_t)(size_t)(DDS_LDS_AS char*)smem;
+  const uint32_t lds_pbuf = lds0 + dg.tab_bytes;
+  const uint32_t lds_wring = lds_pbuf + (PS > 0 ? 2 : 1) * pbuf_bytes;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: everything derived from it stays in SGPRs
+  const int wave_m = wave % (BM / WM), wave_n = wave / (BM / WM);
+  const int tiles_per_img = g.tiles_w * g.tiles_h;
+  const int grp = blockIdx.x / tiles_per_img, tin = blockIdx.x - grp * tiles_per_img;
+  const int th_idx = tin / g.tiles_w, tw_idx = tin - th_idx * g.tiles_w;
+  const int img0 = grp * g.imgs, h0 = th_idx << g.th_log, w0 = tw_idx << g.tw_log;
+  const int n0 = blockIdx.y * BN;
+  const int TWm = (1 << g.tw_log) - 1, THm = (1 << g.th_log) - 1;
+  const int nchunks = (p.Cx * ES) / 128;
+  const size_t pixbytes = (size_t)p.Cx * ES;
+
+  // pixel-offset table of the patch rows: pixel index in the gathered tensor, or -1 (zero row)
+  for (int row = tid; row < prow; row += 256) {
+    int v = -1;
+    if (row < g.patch_pix) {
+      const int im = row / g.PP, rem = row - im * g.PP;
+      const int yy = rem / g.PW, xx = rem - yy * g.PW;
+      const int gi = img0 + im, gh = h0 + yy - 1, gw = w0 + xx - 1;
+      if (gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W) v = (gi * p.H + gh) * p.W + gw;
+    }
+    tab[row] = v;
+  }
+  __syncthreads();
+
+  const int l8 = lane >> 3;
+  const int c16 = ((lane & 7) ^ l8) * 16;  // global 16-byte column this lane fetches (row & 7 == l8)
+  const char* zsrc = (const char*)p.zeros + c16;
+  const int pw_total = prow >> 3;  // wave fills in a patch
+  const uint32_t lds_dump = lds_wring + 3 * (BN * 128);  // 1 KiB that absorbs surplus fills
+  const int tab_lane = l8 * 4;
+  auto fill_patch = [&](int j, int chunk, int buf) {  // j-th fill of this wave; surplus ones go to the dump block
+    const int wl = wave + 4 * j;
+    const bool live = wl < pw_total;  // wave-uniform
+    const int off = *(const int*)((const char*)tab + (live ? wl * 32 : 0) + tab_lane);
+    const char* src = off >= 0 ? (const char*)p.x + (size_t)off * pixbytes + (size_t)chunk * 128 + c16 : zsrc;
+    dma16(src, live ? lds_pbuf + buf * pbuf_bytes + wl * 1024 : lds_dump);
+  };
+  const char* wsrc[WL];
+  bool wok[WL];
+#pragma unroll
+  for (int u = 0; u < WL; ++u) {
+    const int gn = n0 + (wave + 4 * u) * 8 + l8;
+    wok[u] = gn < p.Nout;
+    wsrc[u] = (const char*)p.w + (size_t)(wok[u] ? gn : 0) * 9 * pixbytes + c16;
+  }
+  auto fill_w = [&](int chunk, int tap, int slot) {
+    const size_t off = (size_t)tap * pixbytes + (size_t)chunk * 128;
+#pragma unroll
+    for (int u = 0; u < WL; ++u)
+      dma16(wok[u] ? wsrc[u] + off : zsrc, lds_wring + slot * (BN * 128) + (wave + 4 * u) * 1024);
+  };
+
+  // fragment addressing
+  int arow[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int m = wave_m * WM + i * 32 + (lane & 31);
+    const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
+    arow[i] = im * g.PP + y * g.PW + x;
+  }
+  const int half = lane >> 5;
+  int boff[NJ][4];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int n = wave_n * WN + j * 32 + (lane & 31);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) boff[j][ks] = n * 128 + (((2 * ks + half) ^ (n & 7)) << 4);
+  }
+
+  f32x16_t acc[NJ][NI];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j)
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
+
+  // prologue: whole first patch, then the weight tiles of stages 0 and 1
+  for (int j = 0; wave + 4 * j < pw_total; ++j) fill_patch(j, 0, 0);
+  fill_w(0, 0, 0);
+  fill_w(0, 1, 1);
+
+  auto compute = [&](int chunk, int tap_r, int tap_s, int slot) {
+    const int tapoff = (g.flip ? 2 - tap_r : tap_r) * g.PW + (g.flip ? 2 - tap_s : tap_s);
+    const char* pb = pbuf + (PS > 0 ? (chunk & 1) * pbuf_bytes : 0);
+    const char* wb = wring + slot * (BN * 128);
+    int aaddr[NI], aswz[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      int base = arow[i];
+      asm volatile("" : "+v"(base));  // keep the per-tap addresses from being hoisted (and spilled) for all nine taps
+      const int r = base + tapoff;
+      aaddr[i] = r * 128;
+      aswz[i] = (r & 7) << 4;
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      uint4 a[NI], b[NJ];
+#pragma unroll
+      for (int i = 0; i < NI; ++i) a[i] = *(const uint4*)(pb + aaddr[i] + (((2 * ks + half) << 4) ^ aswz[i]));
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) b[j] = *(const uint4*)(wb + boff[j][ks]);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int i = 0; i < NI; ++i) mfma16B<T>(b[j], a[i], acc[j][i]);
+    }
+  };
+
+// One stage = one tap of one channel chunk. VM = fills per lane issued after the weight
+// tile this stage consumes: one weight tile plus the patch slices of the two previous stages.
+#define DDS_STAGE(TAP)                                                                              \
+  {                                                                                                 \
+    constexpr int VM = WL + PS * (((TAP) >= 2 && (TAP) <= 8 ? 1 : 0) + ((TAP) >= 1 && (TAP) <= 7 ? 1 : 0)); \
+    wait_vm<VM>();                                                                                  \
+    wg_barrier();                                                                                   \
+    {                                                                                               \
+      int ct = chunk + ((TAP) + 2 >= 9 ? 1 : 0), tt = ((TAP) + 2) % 9;                             \
+      if (ct >= nchunks) { ct = nchunks - 1; tt = 8; }                                              \
+      fill_w(ct, tt, ((TAP) + 2) % 3);                                                              \
+    }                                                                                               \
+    if (PS > 0 && (TAP) < 7) {                                                                      \
+      const int cn = chunk + 1 < nchunks ? chunk + 1 : chunk;                                       \
+      _Pragma("unroll") for (int u = 0; u < PS; ++u) fill_patch((TAP) * PS + u, cn, (chunk + 1) & 1); \
+    }                                                                                               \
+    compute(chunk, (TAP) / 3, (TAP) % 3, (TAP) % 3);                                                \
+  }
+
+  for (int chunk = 0; chunk < nchunks; ++chunk) {
+    DDS_STAGE(0) DDS_STAGE(1) DDS_STAGE(2) DDS_STAGE(3) DDS_STAGE(4) DDS_STAGE(5) DDS_STAGE(6) DDS_STAGE(7) DDS_STAGE(8)
+  }
+#undef DDS_STAGE
+  wait_vm<0>();
+
+  const int nb = n0 + wave_n * WN + 4 * (lane >> 5);
+  float bias[NJ][4][4];
+  load_bias_groups<NJ>(p, nb, bias);
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int m = wave_m * WM + i * 32 + (lane & 31);
+    const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
+    const int gi = img0 + im;
+    const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
+    epilogue_tile<T, NJ, NI>(p, acc, i, gi < p.Nimg, pix, nb, bias);
+  }
+}
+
 inline int ilog2_exact(int v) {
   int l = 0;
   while ((1 << l) < v) ++l;
@@ -472,20 +662,20 @@ inline int ilog2_exact(int v) {
 
 // Fills g and returns true when the halo kernel covers this problem.
 template <typename T>
-bool halo_geometry(const ConvParams& p, HaloGeom& g) {
-  constexpr int CK = 64 / sizeof(T);
+bool halo_geometry(const ConvParams& p, HaloGeom& g, int BM = 256, int chunk_bytes = 64) {
+  const int CK = chunk_bytes / (int)sizeof(T);
   if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1 || p.H != p.Ho || p.W != p.Wo) return false;
   if (p.Cx % CK != 0 || p.out_f32) return false;
   const int lw = ilog2_exact(p.W), lh = ilog2_exact(p.H);
   if (lw < 1 || lh < 1 || p.W > 32) return false;
   int TW = p.W, TH, imgs;
-  if (p.H * p.W >= 256) {
-    TH = 256 / TW;
+  if (p.H * p.W >= BM) {
+    TH = BM / TW;
     imgs = 1;
-    if (TH > p.H || p.H % TH) return false;
+    if (TH < 1 || TH > p.H || p.H % TH) return false;
   } else {
     TH = p.H;
-    imgs = 256 / (p.H * p.W);
+    imgs = BM / (p.H * p.W);
   }
   g.tw_log = ilog2_exact(TW);
   g.th_log = ilog2_exact(TH);
@@ -498,6 +688,51 @@ bool halo_geometry(const ConvParams& p, HaloGeom& g) {
   g.patch_bytes = (g.patch_pix * 144 + 255) / 256 * 256;
   g.flip = p.dgrad;
   return true;
+}
+
+template <typename T, int BM, int BN, int WM, int WN, int PS>
+bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
+  DmaGeom dg;
+  dg.h = h;
+  dg.patch_rows = (h.patch_pix + 7) / 8 * 8;
+  dg.tab_bytes = (dg.patch_rows * 4 + 1023) / 1024 * 1024;
+  const int fills_per_wave = (dg.patch_rows / 8 + 3) / 4;
+  const int nchunks = p.Cx * (int)sizeof(T) / 128;
+  if (PS == 0 ? nchunks != 1 : (nchunks < 2 || 7 * PS < fills_per_wave)) return false;
+  const int smem = dg.tab_bytes + (PS > 0 ? 2 : 1) * dg.patch_rows * 128 + 3 * BN * 128 + 1024;
+  if (smem > 160 * 1024 || p.zeros == nullptr) return false;
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)conv3x3_dma_kernel<T, BM, BN, WM, WN, PS>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_set = true;
+  }
+  const int groups = (p.Nimg + h.imgs - 1) / h.imgs;
+  dim3 grid(groups * h.tiles_w * h.tiles_h, (p.ldy + BN - 1) / BN);
+  conv3x3_dma_kernel<T, BM, BN, WM, WN, PS><<<grid, 256, smem, s>>>(p, dg);
+  return true;
+}
+
+// Picks the tile for the asynchronous kernel; false if the problem is outside its range.
+template <typename T>
+bool launch_dma(const ConvParams& p, hipStream_t s) {
+  HaloGeom h;
+  const int nchunks = p.Cx * (int)sizeof(T) / 128;
+  if (p.Cx * (int)sizeof(T) % 128 != 0 || nchunks < 1) return false;
+  if (nchunks == 1) {
+    if (!halo_geometry<T>(p, h, 256, 128)) return false;
+    if (p.ldy <= 64) return launch_dma_inst<T, 256, 64, 64, 64, 0>(p, h, s);
+    return launch_dma_inst<T, 256, 128, 128, 64, 0>(p, h, s);
+  }
+  // small images: 128-pixel tiles keep two patch buffers inside LDS and give more workgroups
+  const long long tiles256 = (long long)((p.M + 255) / 256) * ((p.ldy + 127) / 128);
+  if (tiles256 >= 256 && halo_geometry<T>(p, h, 256, 128)) {
+    if (launch_dma_inst<T, 256, 128, 128, 64, 2>(p, h, s)) return true;
+    if (launch_dma_inst<T, 256, 128, 128, 64, 3>(p, h, s)) return true;
+  }
+  if (halo_geometry<T>(p, h, 128, 128)) {
+    if (launch_dma_inst<T, 128, 128, 64, 64, 2>(p, h, s)) return true;
+  }
+  return false;
 }
 
 template <typename T, int BN, int WM, int WN, int BKB>
@@ -680,6 +915,161 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradParams p) {
   }
 }
 
+// ------------------------------------------------------------------ 3x3 stride-1 wgrad, asynchronous LDS fills + LDS transpose reads (bf16)
+// dW[k][tap][c] = sum over pixels p of dY[p][k] * X[p + tap][c]. The workgroup owns a
+// 64(k) x 64(c) block for ALL nine taps and walks its split of the pixel axis in tiles of
+// 128 pixels (rows of one image, or whole small images): per tile the dY rows and the X
+// patch with halo are copied global -> LDS in their natural [pixel][channel] order (ring
+// of three tiles, filled two tiles ahead) and the nine taps reuse them. The reduction
+// index of this GEMM is the pixel, which is the slow axis of both operands in memory:
+// ds_read_b64_tr_b16 hands each lane four pixels of one channel from a 4 x 16 block, so
+// no register or LDS transposition is needed. 16-byte LDS columns are XOR-ed with
+// 2*(row & 3) so that the four rows of such a block sit on different banks.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint2 lds_tr16(const char* p) {
+  s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t DDS_LDS_AS*)p);
+  return __builtin_bit_cast(uint2, v);
+}
+
+template <int TWLOG, int PF>
+__global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, HaloGeom g, const void* zeros) {
+  constexpr int TW = 1 << TWLOG, PW = TW + 2;
+  constexpr int NF = 4 + PF;  // fills per lane per tile: 4 (dY) + PF (patch; surplus ones go to a dump block)
+  constexpr int TAB = PF > 7 ? 2048 : 1024;
+  extern __shared__ __align__(16) char smem[];
+  const int prow = (g.patch_pix + 7) / 8 * 8;
+  const int slot_bytes = 16384 + prow * 128;
+  int* tab = (int*)smem;                       // packed (im, yy, xx) of every patch row
+  char* ring = smem + TAB;
+  const uint32_t lds_ring = (uint32_t)(size_t)(DDS_LDS_AS char*)smem + TAB;
+  const uint32_t lds_dump = lds_ring + 3 * slot_bytes;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_m = wave & 1, wave_n = wave >> 1;
+  const int k0 = blockIdx.x * 64, c0 = blockIdx.y * 64, z = blockIdx.z;
+  const int tiles_per_img = g.tiles_h;         // TW == image width
+  const int THm = (1 << g.th_log) - 1;
+  const int tile0 = z * (p.pix_per_split >> 7);
+  const int ntiles = p.pix_per_split >> 7;
+  const size_t ybytes = (size_t)p.ldy * 2, xbytes = (size_t)p.Cx * 2;
+
+  for (int row = tid; row < prow; row += 256) {
+    int v = -1;
+    if (row < g.patch_pix) {
+      const int im = row / g.PP, rem = row - im * g.PP;
+      const int yy = rem / PW, xx = rem - yy * PW;
+      v = (im << 16) | (yy << 8) | xx;
+    }
+    tab[row] = v;
+  }
+  __syncthreads();
+
+  const int l8 = lane >> 3;
+  const int c16 = ((lane & 7) ^ ((l8 & 3) << 1)) * 16;  // global 16-byte column for LDS slot lane&7 of a row with row&3 == l8&3
+  const char* zsrc = (const char*)zeros + c16;
+  const int pw_total = prow >> 3;
+  const bool ycol_ok = k0 + (c16 >> 1) < p.ldy;   // this lane's 8 output channels exist
+  auto fill_tile = [&](int t, int slot) {  // t: tile index inside this split (fills nothing real past the end)
+    const bool live_t = t < ntiles;
+    const int tl = tile0 + (live_t ? t : 0);
+    const int grp = tl / tiles_per_img, tin = tl - grp * tiles_per_img;
+    const int img0 = grp * g.imgs, h0 = tin << g.th_log;
+    const uint32_t base = lds_ring + slot * slot_bytes;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // dY rows: tile pixel m = 8*(wave+4u) + l8
+      const int m = (wave + 4 * u) * 8 + l8;
+      const int x = m & (TW - 1), y = (m >> TWLOG) & THm, im = m >> (TWLOG + g.th_log);
+      const int gi = img0 + im;
+      const bool ok = live_t && ycol_ok && gi < p.Nimg;
+      const char* src = ok ? (const char*)p.dy + ((size_t)(gi * p.H + h0 + y) * p.W + x) * ybytes + (size_t)k0 * 2 + c16 : zsrc;
+      dma16(src, live_t ? base + (wave + 4 * u) * 1024 : lds_dump);
+    }
+#pragma unroll
+    for (int u = 0; u < PF; ++u) {  // patch rows
+      const int wl = wave + 4 * u;
+      const bool live = live_t && wl < pw_total;
+      const int pk = *(const int*)((const char*)tab + (live ? wl * 32 : 0) + l8 * 4);
+      const int im = pk >> 16, yy = (pk >> 8) & 255, xx = pk & 255;
+      const int gi = img0 + im, gh = h0 + yy - 1, gw = xx - 1;
+      const bool ok = live && pk >= 0 && gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W;
+      const char* src = ok ? (const char*)p.x + ((size_t)(gi * p.H + gh) * p.W + gw) * xbytes + (size_t)c0 * 2 + c16 : zsrc;
+      dma16(src, live ? base + 16384 + wl * 1024 : lds_dump);
+    }
+  };
+
+  // fragment addressing (see lds_tr16): lane -> (16-lane group, row inside the 4-row block, 8-byte segment)
+  const int lq = lane & 15, grp16 = (lane >> 4) & 1, khalf = lane >> 5;
+  const int rsub = lq >> 2, seg = lq & 3;
+  // A (dY): rows are tile pixels; row & 3 == rsub for every block this lane reads
+  const int a_c = 4 * wave_m + 2 * grp16 + (seg >> 1);
+  const int a_lane = (8 * khalf + rsub) * 128 + ((a_c ^ (rsub << 1)) << 4) + 8 * (seg & 1);
+  const int b_c = 4 * wave_n + 2 * grp16 + (seg >> 1);
+  const int b_off8 = 8 * (seg & 1);
+
+  f32x16_t acc[9], accb;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) accb[e] = 0.f;
+  const uint4 ones = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+
+  fill_tile(0, 0);
+  fill_tile(1, 1);
+  for (int t = 0; t < ntiles; ++t) {
+    wait_vm<NF>();  // everything but the youngest tile's fills has landed
+    wg_barrier();
+    fill_tile(t + 2, (t + 2) % 3);
+    const char* ybuf = ring + (t % 3) * slot_bytes;
+    const char* xbuf = ybuf + 16384;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {  // 16 pixels per step
+      // patch rows of this lane's pixels q and q+4
+      int vb[2][4];  // [which half][row & 3 shift] -> byte address of the (tap-less) block row
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        int q = ks * 16 + 8 * khalf + rsub + 4 * hh;
+        asm volatile("" : "+v"(q));
+        const int x = q & (TW - 1), y = (q >> TWLOG) & THm, im = q >> (TWLOG + g.th_log);
+        const int R = im * g.PP + y * PW + x;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) vb[hh][d] = R * 128 + ((b_c ^ (((R + d) & 3) << 1)) << 4) + b_off8;
+      }
+      uint2 a0 = lds_tr16(ybuf + a_lane + ks * 2048);
+      uint2 a1 = lds_tr16(ybuf + a_lane + ks * 2048 + 512);
+      const uint4 af = make_uint4(a0.x, a0.y, a1.x, a1.y);
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        constexpr int dummy = 0; (void)dummy;
+        const int tr = tap / 3, ts = tap % 3;
+        const int toff = tr * PW + ts;       // compile-time; PW & 3 == 2 for every supported width
+        const int d = toff & 3;
+        uint2 b0 = lds_tr16(xbuf + vb[0][d] + toff * 128);
+        uint2 b1 = lds_tr16(xbuf + vb[1][d] + toff * 128);
+        const uint4 bf = make_uint4(b0.x, b0.y, b1.x, b1.y);
+        mfma16B<bf16_t>(af, bf, acc[tap]);
+      }
+      if (wave_n == 0) mfma16B<bf16_t>(af, ones, accb);
+    }
+  }
+  wait_vm<0>();
+
+  float* out = p.partial + (size_t)z * p.Pl;
+  const int cin = c0 + wave_n * 32 + (lane & 31);
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int k = k0 + wave_m * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+    if (k >= p.Mout) continue;
+    if (cin < p.Cx) {
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) out[(size_t)k * p.NK + tap * p.Cx + cin] = p.alpha * acc[tap][e];
+    }
+    if (wave_n == 0 && (lane & 31) == 0 && blockIdx.y == 0) out[(size_t)p.Mout * p.NK + k] = p.alpha * accb[e];
+  }
+}
+
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
 #ifndef HALO_BKB
@@ -688,6 +1078,7 @@ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 template <typename T>
 void launch_conv_t(const ConvParams& p, hipStream_t s) {
   constexpr int BKB = 64;
+  if (launch_dma<T>(p, s)) return;
   HaloGeom g;
   if (halo_geometry<T>(p, g)) {
     if (p.ldy <= 64) launch_halo_inst<T, 64, 64, 64, HALO_BKB>(p, g, s);
@@ -705,9 +1096,46 @@ void launch_conv_t(const ConvParams& p, hipStream_t s) {
   }
 }
 
+template <int TWLOG, int PF>
+void launch_wgrad_dma_inst(const WgradParams& p, const HaloGeom& g, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    (void)hipFuncSetAttribute((const void*)wgrad3x3_dma_kernel<TWLOG, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    attr_set = true;
+  }
+  const int prow = (g.patch_pix + 7) / 8 * 8;
+  const int smem = (PF > 7 ? 2048 : 1024) + 3 * (16384 + prow * 128) + 1024;
+  dim3 grid(cdiv(p.Mout, 64), p.Cx / 64, p.nsplit);
+  wgrad3x3_dma_kernel<TWLOG, PF><<<grid, 256, smem, s>>>(p, g, p.zeros);
+}
+
+// bf16 3x3 stride-1 problems whose splits are whole 128-pixel tiles go to the asynchronous kernel
+bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
+  if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1 || p.H != p.Ho || p.W != p.Wo) return false;
+  if (p.Cx % 64 != 0 || p.zeros == nullptr || p.pix_per_split % 128 != 0 || p.P % 128 != 0) return false;
+  ConvParams c{};
+  c.R = c.S = 3; c.stride = 1; c.pad = 1; c.H = c.Ho = p.H; c.W = c.Wo = p.W; c.Cx = p.Cx; c.out_f32 = 0; c.dgrad = 0;
+  HaloGeom g;
+  if (!halo_geometry<bf16_t>(c, g, 128, 128)) return false;
+  const int prow = (g.patch_pix + 7) / 8 * 8;
+  const int fills = (prow / 8 + 3) / 4;  // patch fills per wave
+  if (fills <= 7) {
+    switch (g.tw_log) {
+      case 2: launch_wgrad_dma_inst<2, 7>(p, g, s); return true;
+      case 3: launch_wgrad_dma_inst<3, 7>(p, g, s); return true;
+      case 4: launch_wgrad_dma_inst<4, 7>(p, g, s); return true;
+      case 5: launch_wgrad_dma_inst<5, 7>(p, g, s); return true;
+      default: return false;
+    }
+  }
+  if (fills <= 9 && prow * 4 <= 2048 && g.tw_log == 2) { launch_wgrad_dma_inst<2, 9>(p, g, s); return true; }
+  return false;
+}
+
 template <typename T>
 void launch_wgrad_t(const WgradParams& p, hipStream_t s) {
   constexpr int CE = 16 / sizeof(T);
+  if (sizeof(T) == 2 && launch_wgrad_dma(p, s)) return;
   if (p.Mout <= 64) {
     dim3 grid(cdiv(p.Mout, 64), cdiv(p.NK + CE, 256), p.nsplit);
     wgrad_gemm_kernel<T, 64, 256, 64, 64><<<grid, 256, 0, s>>>(p);

@@ -26,6 +26,7 @@ struct ConvParams {
   const float* bias;  // fp32 [Nout] or null
   const void* res;    // same layout as y (dtype T) or null
   const void* mask;   // same layout as y (dtype T) or null
+  const void* zeros;  // at least 256 zero bytes (source of padding rows for LDS fills)
   int Nimg, H, W, Cx; // gathered tensor: NHWC, channel stride Cx (= GEMM-K per tap)
   int Ho, Wo;         // pixel grid of y; M = Nimg*Ho*Wo
   int M;
@@ -47,6 +48,7 @@ struct WgradParams {
   const void* dy;   // [P][ldy]
   const void* x;    // [Nimg][H][W][Cx]
   float* partial;   // [nsplit][Pl]
+  const void* zeros; // at least 256 zero bytes
   int Nimg, H, W, Cx, Ho, Wo;
   int Mout;         // real output channels
   int ldy;
