@@ -81,10 +81,17 @@ template <typename T> __device__ __forceinline__ void store4(void* p, size_t i, 
 template <> __device__ __forceinline__ void store4<float>(void* p, size_t i, const float* v) {
   *(float4*)((float*)p + i) = make_float4(v[0], v[1], v[2], v[3]);
 }
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+// two floats -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
 template <> __device__ __forceinline__ void store4<bf16_t>(void* p, size_t i, const float* v) {
   uint2 t;
-  t.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-  t.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+  t.x = pack_bf16(v[0], v[1]);
+  t.y = pack_bf16(v[2], v[3]);
   *(uint2*)((uint16_t*)p + i) = t;
 }
 
@@ -120,13 +127,19 @@ __device__ __forceinline__ void load_bias_groups(const ConvParams& p, int nb, fl
       }
 }
 
+// res_lds / mask_lds: if non-null the tile's residual / mask values were staged in LDS as
+// [tile row][row_bytes] with 16-byte column c of row m stored at column c ^ (m & (ncol-1));
+// tile_row is this lane's row, ncol = row_bytes / 16, nloc0 the lane's first channel inside the tile.
 template <typename T, int NJ, int NI>
 __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_t (&acc)[NJ][NI], int i, bool valid,
-                                              size_t pix, int nb, const float (&bias)[NJ][4][4]) {
+                                              size_t pix, int nb, const float (&bias)[NJ][4][4],
+                                              const char* res_lds = nullptr, const char* mask_lds = nullptr,
+                                              int tile_row = 0, int row_bytes = 0, int nloc0 = 0) {
   typedef typename Raw4<T>::type raw_t;
   size_t o[NJ][4];
   bool ok[NJ][4];
   raw_t r[NJ][4], mk[NJ][4];
+  const int ncolm = (row_bytes >> 4) - 1;
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -135,17 +148,23 @@ __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_
       ok[j][g] = valid && n < p.ldy;
       o[j][g] = ok[j][g] ? pix * p.ldy + n : 0;
     }
+  auto lds_at = [&](const char* base, int j, int g) {
+    const int bytecol = (nloc0 + 32 * j + 8 * g) * (int)sizeof(T);
+    return base + tile_row * row_bytes + ((((bytecol >> 4) ^ tile_row) & ncolm) << 4) + (bytecol & 15);
+  };
   if (p.res) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) r[j][g] = *(const raw_t*)((const T*)p.res + o[j][g]);
+      for (int g = 0; g < 4; ++g)
+        r[j][g] = res_lds ? *(const raw_t*)lds_at(res_lds, j, g) : *(const raw_t*)((const T*)p.res + o[j][g]);
   }
   if (p.mask) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) mk[j][g] = *(const raw_t*)((const T*)p.mask + o[j][g]);
+      for (int g = 0; g < 4; ++g)
+        mk[j][g] = mask_lds ? *(const raw_t*)lds_at(mask_lds, j, g) : *(const raw_t*)((const T*)p.mask + o[j][g]);
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
@@ -225,32 +244,34 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p) {
   int kc = chunk * CE, kr = 0, ks = 0, kflat = chunk * CE;
   while (kc >= p.Cx) { kc -= p.Cx; if (++ks == p.S) { ks = 0; ++kr; } }
 
+  // Loads are unconditional (out-of-range taps read the tensor base and are zeroed when
+  // parked in LDS): a branch around a load would make the compiler drain every
+  // outstanding load at each use.
   uint4 ra[AP], rb[BP];
+  bool oka[AP], okb[BP];
   auto load_global = [&]() {
 #pragma unroll
     for (int i = 0; i < AP; ++i) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (a_ok[i] && kr < p.R) {
-        int hi, wi;
-        bool ok;
-        if (DGRAD) {
-          int nh = a_h[i] - kr, nw = a_w[i] - ks;
-          ok = nh >= 0 && nw >= 0 && ((nh | nw) & sh) == 0;
-          hi = nh >> sh; wi = nw >> sh;
-          ok = ok && hi < p.H && wi < p.W;
-        } else {
-          hi = a_h[i] + kr; wi = a_w[i] + ks;
-          ok = (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
-        }
-        if (ok) v = *(const uint4*)(a_base[i] + ((size_t)(hi * p.W + wi) * p.Cx + kc) * ES);
+      int hi, wi;
+      bool ok;
+      if (DGRAD) {
+        int nh = a_h[i] - kr, nw = a_w[i] - ks;
+        ok = nh >= 0 && nw >= 0 && ((nh | nw) & sh) == 0;
+        hi = nh >> sh; wi = nw >> sh;
+        ok = ok && hi < p.H && wi < p.W;
+      } else {
+        hi = a_h[i] + kr; wi = a_w[i] + ks;
+        ok = (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
       }
-      ra[i] = v;
+      ok = ok && a_ok[i] && kr < p.R;
+      oka[i] = ok;
+      const size_t off = ok ? ((size_t)(hi * p.W + wi) * p.Cx + kc) * ES : 0;
+      ra[i] = *(const uint4*)(a_base[i] + off);
     }
 #pragma unroll
     for (int i = 0; i < BP; ++i) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (b_ok[i] && kflat < p.Ktot) v = *(const uint4*)(b_base[i] + (size_t)kflat * ES);
-      rb[i] = v;
+      okb[i] = b_ok[i] && kflat < p.Ktot;
+      rb[i] = *(const uint4*)(b_base[i] + (size_t)(okb[i] ? kflat : 0) * ES);
     }
     kflat += BKE;
     kc += BKE;
@@ -260,9 +281,9 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p) {
     char* As = smem + buf * (BM + BN) * LDK;
     char* Bs = As + BM * LDK;
 #pragma unroll
-    for (int i = 0; i < AP; ++i) *(uint4*)(As + (rbase + i * ROWS) * LDK + chunk * 16) = ra[i];
+    for (int i = 0; i < AP; ++i) *(uint4*)(As + (rbase + i * ROWS) * LDK + chunk * 16) = keep_if(oka[i], ra[i]);
 #pragma unroll
-    for (int i = 0; i < BP; ++i) *(uint4*)(Bs + (rbase + i * ROWS) * LDK + chunk * 16) = rb[i];
+    for (int i = 0; i < BP; ++i) *(uint4*)(Bs + (rbase + i * ROWS) * LDK + chunk * 16) = keep_if(okb[i], rb[i]);
   };
 
   f32x16_t acc[WN / 32][WM / 32];
@@ -487,6 +508,7 @@ struct DmaGeom {
   HaloGeom h;
   int patch_rows;   // patch pixels rounded up to 8 (one wave fill = 8 rows)
   int tab_bytes;    // pixel-offset table, rounded to 1 KiB
+  int smem_bytes;   // dynamic LDS of the launch
 };
 
 template <typename T, int BM, int BN, int WM, int WN, int PS>
@@ -641,6 +663,42 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
 #undef DDS_STAGE
   wait_vm<0>();
 
+  // Stage the residual / mask tiles of this workgroup in LDS (the operand buffers are free
+  // now) so the epilogue pays one global round trip instead of one per 32-pixel column.
+  constexpr int ROWB = BN * ES;        // bytes per tile row
+  constexpr int NCOL = ROWB / 16;      // 16-byte columns per row
+  constexpr int RPF = 64 / NCOL;       // rows per wave fill
+  constexpr int FPW = BM / RPF / 4;    // fills per wave
+  const char* res_lds = nullptr;
+  const char* mask_lds = nullptr;
+  if (p.res || p.mask) {
+    wg_barrier();
+    int region = 0;
+    auto stage_tile = [&](const void* src_tensor) -> const char* {
+      if ((region + 1) * BM * ROWB > dg.smem_bytes) return nullptr;
+      const int rbase = region * BM * ROWB;
+#pragma unroll
+      for (int u = 0; u < FPW; ++u) {
+        const int f = wave + 4 * u;
+        const int row = f * RPF + lane / NCOL, slot = lane % NCOL;
+        const int gc = (slot ^ row) & (NCOL - 1);
+        const int x = row & TWm, y = (row >> g.tw_log) & THm, im = row >> (g.tw_log + g.th_log);
+        const int gi = img0 + im;
+        const int n = n0 + gc * (16 / ES);
+        const bool ok = gi < p.Nimg && n < p.ldy;
+        const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
+        const char* src = ok ? (const char*)src_tensor + (pix * p.ldy + n) * ES : (const char*)p.zeros;
+        dma16(src, lds0 + rbase + f * 1024);
+      }
+      ++region;
+      return smem + rbase;
+    };
+    if (p.mask) mask_lds = stage_tile(p.mask);
+    if (p.res) res_lds = stage_tile(p.res);
+    wait_vm<0>();
+    wg_barrier();
+  }
+
   const int nb = n0 + wave_n * WN + 4 * (lane >> 5);
   float bias[NJ][4][4];
   load_bias_groups<NJ>(p, nb, bias);
@@ -650,7 +708,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
     const int gi = img0 + im;
     const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
-    epilogue_tile<T, NJ, NI>(p, acc, i, gi < p.Nimg, pix, nb, bias);
+    epilogue_tile<T, NJ, NI>(p, acc, i, gi < p.Nimg, pix, nb, bias, res_lds, mask_lds, m, ROWB, wave_n * WN + 4 * (lane >> 5));
   }
 }
 
@@ -701,6 +759,7 @@ bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
   if (PS == 0 ? nchunks != 1 : (nchunks < 2 || 7 * PS < fills_per_wave)) return false;
   const int smem = dg.tab_bytes + (PS > 0 ? 2 : 1) * dg.patch_rows * 128 + 3 * BN * 128 + 1024;
   if (smem > 160 * 1024 || p.zeros == nullptr) return false;
+  dg.smem_bytes = smem;
   static bool attr_set = false;
   if (!attr_set) {
     (void)hipFuncSetAttribute((const void*)conv3x3_dma_kernel<T, BM, BN, WM, WN, PS>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
@@ -834,29 +893,36 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradParams p) {
     }
   }
 
+  // unconditional loads from clamped addresses; validity is applied when the data is parked in LDS
   uint4 regs[NBLK][CE];
+  uint32_t okmask[NBLK], onemask[NBLK];
   auto load_global = [&](int ptile) {
 #pragma unroll
     for (int b = 0; b < NBLK; ++b) {
+      okmask[b] = 0;
+      onemask[b] = 0;
 #pragma unroll
       for (int g = 0; g < CE; ++g) {
         const int pix = ptile + kg[b] * CE + g;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (pix < pz1) {
-          if (isA[b]) {
-            if (okc[b]) v = *(const uint4*)((const char*)p.dy + ((size_t)pix * p.ldy + coff[b]) * ES);
-          } else if (okc[b]) {
-            int img = pix / HoWo;
-            int rem = pix - img * HoWo;
-            int oh = rem / p.Wo, ow = rem - oh * p.Wo;
-            int hi = oh * p.stride + bh[b], wi = ow * p.stride + bw[b];
-            if ((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W)
-              v = *(const uint4*)((const char*)p.x + (((size_t)img * p.H + hi) * p.W + wi) * p.Cx * ES + (size_t)coff[b] * ES);
-          } else if (isBias[b]) {
-            v = one_chunk<T>();
-          }
+        const bool inr = pix < pz1;
+        const char* src = (const char*)p.dy;
+        bool ok = false;
+        if (isA[b]) {
+          ok = inr && okc[b];
+          if (ok) src = (const char*)p.dy + ((size_t)pix * p.ldy + coff[b]) * ES;
+        } else if (okc[b]) {
+          const int pp = inr ? pix : 0;
+          int img = pp / HoWo;
+          int rem = pp - img * HoWo;
+          int oh = rem / p.Wo, ow = rem - oh * p.Wo;
+          int hi = oh * p.stride + bh[b], wi = ow * p.stride + bw[b];
+          ok = inr && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
+          if (ok) src = (const char*)p.x + (((size_t)img * p.H + hi) * p.W + wi) * p.Cx * ES + (size_t)coff[b] * ES;
+        } else if (isBias[b] && inr) {
+          onemask[b] |= 1u << g;
         }
-        regs[b][g] = v;
+        okmask[b] |= (ok ? 1u : 0u) << g;
+        regs[b][g] = *(const uint4*)src;
       }
     }
   };
@@ -865,8 +931,13 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradParams p) {
 #pragma unroll
     for (int b = 0; b < NBLK; ++b) {
       if (row0[b] < 0) continue;
-      uint4 t[CE];
-      transpose_chunks<T>(regs[b], t);
+      uint4 sel[CE], t[CE];
+#pragma unroll
+      for (int g = 0; g < CE; ++g) {
+        sel[g] = keep_if((okmask[b] >> g) & 1u, regs[b][g]);
+        if ((onemask[b] >> g) & 1u) sel[g] = one_chunk<T>();
+      }
+      transpose_chunks<T>(sel, t);
 #pragma unroll
       for (int e = 0; e < CE; ++e) *(uint4*)(base + (row0[b] + e) * LDK + kg[b] * 16) = t[e];
     }
