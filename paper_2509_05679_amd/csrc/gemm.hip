@@ -511,16 +511,20 @@ struct DmaGeom {
   int smem_bytes;   // dynamic LDS of the launch
 };
 
-template <typename T, int BM, int BN, int WM, int WN, int PS>
+template <typename T, int BM, int BN, int WM, int WN, int PS, int KB>
 __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGeom dg) {
   constexpr int ES = sizeof(T);
-  constexpr int WL = BN / 32;  // weight fills per lane per stage
+  constexpr int FROWS = 1024 / KB;     // LDS rows per wave fill (KB = bytes of channels per row: 64 or 128)
+  constexpr int CPR = KB / 16;         // 16-byte columns per row
+  constexpr int WL = BN / FROWS / 4;   // weight fills per lane per stage
+  constexpr int NKS = KB / 32;         // MFMA k-steps per stage
+  static_assert(WL >= 1, "weight tile smaller than one fill per wave");
   constexpr int NI = WM / 32, NJ = WN / 32;
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
   extern __shared__ __align__(16) char smem[];
   const HaloGeom& g = dg.h;
   const int prow = dg.patch_rows;
-  const int pbuf_bytes = prow * 128;
+  const int pbuf_bytes = prow * KB;
   int* tab = (int*)smem;
   char* pbuf = smem + dg.tab_bytes;
   char* wring = pbuf + (PS > 0 ? 2 : 1) * pbuf_bytes;
@@ -537,7 +541,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   const int img0 = grp * g.imgs, h0 = th_idx << g.th_log, w0 = tw_idx << g.tw_log;
   const int n0 = blockIdx.y * BN;
   const int TWm = (1 << g.tw_log) - 1, THm = (1 << g.th_log) - 1;
-  const int nchunks = (p.Cx * ES) / 128;
+  const int nchunks = (p.Cx * ES) / KB;
   const size_t pixbytes = (size_t)p.Cx * ES;
 
   // pixel-offset table of the patch rows: pixel index in the gathered tensor, or -1 (zero row)
@@ -553,32 +557,34 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   }
   __syncthreads();
 
-  const int l8 = lane >> 3;
-  const int c16 = ((lane & 7) ^ l8) * 16;  // global 16-byte column this lane fetches (row & 7 == l8)
+  // column swizzle of a row: eight (KB=128) or four (KB=64) consecutive rows land on distinct banks
+  auto swz = [](int r) { return KB == 128 ? (r & 7) : ((r >> 1) & 3); };
+  const int l8 = lane / CPR;  // row inside a fill
+  const int c16 = ((lane % CPR) ^ swz(l8)) * 16;  // global 16-byte column this lane fetches (fills start at multiples of FROWS rows)
   const char* zsrc = (const char*)p.zeros + c16;
-  const int pw_total = prow >> 3;  // wave fills in a patch
-  const uint32_t lds_dump = lds_wring + 3 * (BN * 128);  // 1 KiB that absorbs surplus fills
+  const int pw_total = prow / FROWS;  // wave fills in a patch
+  const uint32_t lds_dump = lds_wring + 3 * (BN * KB);  // 1 KiB that absorbs surplus fills
   const int tab_lane = l8 * 4;
   auto fill_patch = [&](int j, int chunk, int buf) {  // j-th fill of this wave; surplus ones go to the dump block
     const int wl = wave + 4 * j;
     const bool live = wl < pw_total;  // wave-uniform
-    const int off = *(const int*)((const char*)tab + (live ? wl * 32 : 0) + tab_lane);
-    const char* src = off >= 0 ? (const char*)p.x + (size_t)off * pixbytes + (size_t)chunk * 128 + c16 : zsrc;
+    const int off = *(const int*)((const char*)tab + (live ? wl * (FROWS * 4) : 0) + tab_lane);
+    const char* src = off >= 0 ? (const char*)p.x + (size_t)off * pixbytes + (size_t)chunk * KB + c16 : zsrc;
     dma16(src, live ? lds_pbuf + buf * pbuf_bytes + wl * 1024 : lds_dump);
   };
   const char* wsrc[WL];
   bool wok[WL];
 #pragma unroll
   for (int u = 0; u < WL; ++u) {
-    const int gn = n0 + (wave + 4 * u) * 8 + l8;
+    const int gn = n0 + (wave + 4 * u) * FROWS + l8;
     wok[u] = gn < p.Nout;
     wsrc[u] = (const char*)p.w + (size_t)(wok[u] ? gn : 0) * 9 * pixbytes + c16;
   }
   auto fill_w = [&](int chunk, int tap, int slot) {
-    const size_t off = (size_t)tap * pixbytes + (size_t)chunk * 128;
+    const size_t off = (size_t)tap * pixbytes + (size_t)chunk * KB;
 #pragma unroll
     for (int u = 0; u < WL; ++u)
-      dma16(wok[u] ? wsrc[u] + off : zsrc, lds_wring + slot * (BN * 128) + (wave + 4 * u) * 1024);
+      dma16(wok[u] ? wsrc[u] + off : zsrc, lds_wring + slot * (BN * KB) + (wave + 4 * u) * 1024);
   };
 
   // fragment addressing
@@ -590,12 +596,12 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     arow[i] = im * g.PP + y * g.PW + x;
   }
   const int half = lane >> 5;
-  int boff[NJ][4];
+  int boff[NJ][NKS];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
     const int n = wave_n * WN + j * 32 + (lane & 31);
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) boff[j][ks] = n * 128 + (((2 * ks + half) ^ (n & 7)) << 4);
+    for (int ks = 0; ks < NKS; ++ks) boff[j][ks] = n * KB + (((2 * ks + half) ^ swz(n)) << 4);
   }
 
   f32x16_t acc[NJ][NI];
@@ -614,18 +620,18 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   auto compute = [&](int chunk, int tap_r, int tap_s, int slot) {
     const int tapoff = (g.flip ? 2 - tap_r : tap_r) * g.PW + (g.flip ? 2 - tap_s : tap_s);
     const char* pb = pbuf + (PS > 0 ? (chunk & 1) * pbuf_bytes : 0);
-    const char* wb = wring + slot * (BN * 128);
+    const char* wb = wring + slot * (BN * KB);
     int aaddr[NI], aswz[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       int base = arow[i];
       asm volatile("" : "+v"(base));  // keep the per-tap addresses from being hoisted (and spilled) for all nine taps
       const int r = base + tapoff;
-      aaddr[i] = r * 128;
-      aswz[i] = (r & 7) << 4;
+      aaddr[i] = r * KB;
+      aswz[i] = swz(r) << 4;
     }
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
+    for (int ks = 0; ks < NKS; ++ks) {
       uint4 a[NI], b[NJ];
 #pragma unroll
       for (int i = 0; i < NI; ++i) a[i] = *(const uint4*)(pb + aaddr[i] + (((2 * ks + half) << 4) ^ aswz[i]));
@@ -748,48 +754,63 @@ bool halo_geometry(const ConvParams& p, HaloGeom& g, int BM = 256, int chunk_byt
   return true;
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int PS>
+template <typename T, int BM, int BN, int WM, int WN, int PS, int KB>
 bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
+  constexpr int FROWS = 1024 / KB;
   DmaGeom dg;
   dg.h = h;
-  dg.patch_rows = (h.patch_pix + 7) / 8 * 8;
+  dg.patch_rows = (h.patch_pix + FROWS - 1) / FROWS * FROWS;
   dg.tab_bytes = (dg.patch_rows * 4 + 1023) / 1024 * 1024;
-  const int fills_per_wave = (dg.patch_rows / 8 + 3) / 4;
-  const int nchunks = p.Cx * (int)sizeof(T) / 128;
+  const int fills_per_wave = (dg.patch_rows / FROWS + 3) / 4;
+  if (p.Cx * (int)sizeof(T) % KB != 0) return false;
+  const int nchunks = p.Cx * (int)sizeof(T) / KB;
   if (PS == 0 ? nchunks != 1 : (nchunks < 2 || 7 * PS < fills_per_wave)) return false;
-  const int smem = dg.tab_bytes + (PS > 0 ? 2 : 1) * dg.patch_rows * 128 + 3 * BN * 128 + 1024;
+  const int smem = dg.tab_bytes + (PS > 0 ? 2 : 1) * dg.patch_rows * KB + 3 * BN * KB + 1024;
   if (smem > 160 * 1024 || p.zeros == nullptr) return false;
   dg.smem_bytes = smem;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)conv3x3_dma_kernel<T, BM, BN, WM, WN, PS>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void*)conv3x3_dma_kernel<T, BM, BN, WM, WN, PS, KB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_set = true;
   }
   const int groups = (p.Nimg + h.imgs - 1) / h.imgs;
   dim3 grid(groups * h.tiles_w * h.tiles_h, (p.ldy + BN - 1) / BN);
-  conv3x3_dma_kernel<T, BM, BN, WM, WN, PS><<<grid, 256, smem, s>>>(p, dg);
+  conv3x3_dma_kernel<T, BM, BN, WM, WN, PS, KB><<<grid, 256, smem, s>>>(p, dg);
   return true;
 }
 
 // Picks the tile for the asynchronous kernel; false if the problem is outside its range.
+// DDS_CONV_KB (64 or 128) is the channel-chunk depth in bytes: 64-byte rows halve the LDS
+// footprint so that two workgroups share a CU and hide each other's prologue and epilogue.
+#ifndef DDS_CONV_KB
+#define DDS_CONV_KB 64
+#endif
 template <typename T>
 bool launch_dma(const ConvParams& p, hipStream_t s) {
   HaloGeom h;
-  const int nchunks = p.Cx * (int)sizeof(T) / 128;
-  if (p.Cx * (int)sizeof(T) % 128 != 0 || nchunks < 1) return false;
+  constexpr int KB = DDS_CONV_KB;
+  const int rowbytes = p.Cx * (int)sizeof(T);
+  if (rowbytes % KB != 0) return false;
+  const int nchunks = rowbytes / KB;
   if (nchunks == 1) {
-    if (!halo_geometry<T>(p, h, 256, 128)) return false;
-    if (p.ldy <= 64) return launch_dma_inst<T, 256, 64, 64, 64, 0>(p, h, s);
-    return launch_dma_inst<T, 256, 128, 128, 64, 0>(p, h, s);
+    if (!halo_geometry<T>(p, h, 256, KB)) return false;
+    if (p.ldy <= 64) return launch_dma_inst<T, 256, 64, 64, 64, 0, KB>(p, h, s);
+    return launch_dma_inst<T, 256, 128, 128, 64, 0, KB>(p, h, s);
   }
-  // small images: 128-pixel tiles keep two patch buffers inside LDS and give more workgroups
+  // small images: 128-pixel tiles give more workgroups
   const long long tiles256 = (long long)((p.M + 255) / 256) * ((p.ldy + 127) / 128);
-  if (tiles256 >= 256 && halo_geometry<T>(p, h, 256, 128)) {
-    if (launch_dma_inst<T, 256, 128, 128, 64, 2>(p, h, s)) return true;
-    if (launch_dma_inst<T, 256, 128, 128, 64, 3>(p, h, s)) return true;
+  if (tiles256 >= 512 && halo_geometry<T>(p, h, 256, KB)) {
+    if (p.ldy <= 64) {
+      if (launch_dma_inst<T, 256, 64, 64, 64, 1, KB>(p, h, s)) return true;
+      if (launch_dma_inst<T, 256, 64, 64, 64, 2, KB>(p, h, s)) return true;
+    }
+    if (launch_dma_inst<T, 256, 128, 128, 64, 1, KB>(p, h, s)) return true;
+    if (launch_dma_inst<T, 256, 128, 128, 64, 2, KB>(p, h, s)) return true;
+    if (launch_dma_inst<T, 256, 128, 128, 64, 3, KB>(p, h, s)) return true;
   }
-  if (halo_geometry<T>(p, h, 128, 128)) {
-    if (launch_dma_inst<T, 128, 128, 64, 64, 2>(p, h, s)) return true;
+  if (halo_geometry<T>(p, h, 128, KB)) {
+    if (launch_dma_inst<T, 128, 128, 64, 64, 1, KB>(p, h, s)) return true;
+    if (launch_dma_inst<T, 128, 128, 64, 64, 2, KB>(p, h, s)) return true;
   }
   return false;
 }
