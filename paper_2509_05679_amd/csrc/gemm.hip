@@ -1031,7 +1031,6 @@ __global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, Hal
   extern __shared__ __align__(16) char smem[];
   const int prow = (g.patch_pix + 7) / 8 * 8;
   const int slot_bytes = 16384 + prow * 128;
-  int* tab = (int*)smem;                       // packed (im, yy, xx) of every patch row
   char* ring = smem + TAB;
   const uint32_t lds_ring = (uint32_t)(size_t)(DDS_LDS_AS char*)smem + TAB;
   const uint32_t lds_dump = lds_ring + 3 * slot_bytes;
@@ -1046,47 +1045,51 @@ __global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, Hal
   const int ntiles = p.pix_per_split >> 7;
   const size_t ybytes = (size_t)p.ldy * 2, xbytes = (size_t)p.Cx * 2;
 
-  for (int row = tid; row < prow; row += 256) {
-    int v = -1;
-    if (row < g.patch_pix) {
-      const int im = row / g.PP, rem = row - im * g.PP;
-      const int yy = rem / PW, xx = rem - yy * PW;
-      v = (im << 16) | (yy << 8) | xx;
-    }
-    tab[row] = v;
-  }
-  __syncthreads();
-
+  // A tile is 128 consecutive pixels of the flattened (image, row, column) index, so the
+  // source address of every fill advances by a constant from tile to tile; what is kept
+  // per lane and fill is the byte offset of its patch row relative to the tile origin and
+  // the row / column facts that decide whether that row is padding.
   const int l8 = lane >> 3;
   const int c16 = ((lane & 7) ^ ((l8 & 3) << 1)) * 16;  // global 16-byte column for LDS slot lane&7 of a row with row&3 == l8&3
   const char* zsrc = (const char*)zeros + c16;
   const int pw_total = prow >> 3;
   const bool ycol_ok = k0 + (c16 >> 1) < p.ldy;   // this lane's 8 output channels exist
+  const size_t tile_ybytes = 128 * ybytes, tile_xbytes = 128 * xbytes;
+  const char* ysrc0 = (const char*)p.dy + ((size_t)tile0 * 128 + (size_t)(wave * 8 + l8)) * ybytes + (size_t)k0 * 2 + c16;
+  const char* xsrc0 = (const char*)p.x + (size_t)tile0 * tile_xbytes + (size_t)c0 * 2 + c16;
+  int prel[PF], pflag[PF];  // byte offset from the tile origin; yy | column valid << 8
+#pragma unroll
+  for (int u = 0; u < PF; ++u) {
+    const int row = (wave + 4 * u) * 8 + l8;
+    int rel = 0, flag = 0;
+    if (row < g.patch_pix) {
+      const int im = row / g.PP, rem = row - im * g.PP;
+      const int yy = rem / PW, xx = rem - yy * PW;
+      rel = (int)((((long long)im * p.H + yy - 1) * p.W + (xx - 1)) * (long long)xbytes);
+      flag = yy | (((unsigned)(xx - 1) < (unsigned)p.W ? 1 : 0) << 8);
+    }
+    prel[u] = rel;
+    pflag[u] = flag;
+  }
+  const int tile_in_img_mask = tiles_per_img - 1;  // tiles per image is a power of two
   auto fill_tile = [&](int t, int slot) {  // t: tile index inside this split (fills nothing real past the end)
     const bool live_t = t < ntiles;
-    const int tl = tile0 + (live_t ? t : 0);
-    const int grp = tl / tiles_per_img, tin = tl - grp * tiles_per_img;
-    const int img0 = grp * g.imgs, h0 = tin << g.th_log;
+    const int tt = live_t ? t : 0;
+    const int h0 = ((tile0 + tt) & tile_in_img_mask) << g.th_log;
     const uint32_t base = lds_ring + slot * slot_bytes;
+    const char* ysrc = ysrc0 + (size_t)tt * tile_ybytes;
+    const char* xsrc = xsrc0 + (size_t)tt * tile_xbytes;
+    const bool yok = live_t && ycol_ok;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {  // dY rows: tile pixel m = 8*(wave+4u) + l8
-      const int m = (wave + 4 * u) * 8 + l8;
-      const int x = m & (TW - 1), y = (m >> TWLOG) & THm, im = m >> (TWLOG + g.th_log);
-      const int gi = img0 + im;
-      const bool ok = live_t && ycol_ok && gi < p.Nimg;
-      const char* src = ok ? (const char*)p.dy + ((size_t)(gi * p.H + h0 + y) * p.W + x) * ybytes + (size_t)k0 * 2 + c16 : zsrc;
-      dma16(src, live_t ? base + (wave + 4 * u) * 1024 : lds_dump);
-    }
+    for (int u = 0; u < 4; ++u)  // dY rows: tile pixel 8*(wave+4u) + l8
+      dma16(yok ? ysrc + (size_t)u * 32 * ybytes : zsrc, live_t ? base + (wave + 4 * u) * 1024 : lds_dump);
 #pragma unroll
     for (int u = 0; u < PF; ++u) {  // patch rows
       const int wl = wave + 4 * u;
       const bool live = live_t && wl < pw_total;
-      const int pk = *(const int*)((const char*)tab + (live ? wl * 32 : 0) + l8 * 4);
-      const int im = pk >> 16, yy = (pk >> 8) & 255, xx = pk & 255;
-      const int gi = img0 + im, gh = h0 + yy - 1, gw = xx - 1;
-      const bool ok = live && pk >= 0 && gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W;
-      const char* src = ok ? (const char*)p.x + ((size_t)(gi * p.H + gh) * p.W + gw) * xbytes + (size_t)c0 * 2 + c16 : zsrc;
-      dma16(src, live ? base + 16384 + wl * 1024 : lds_dump);
+      const int gh = h0 + (pflag[u] & 255) - 1;
+      const bool ok = live && (pflag[u] >> 8) && (unsigned)gh < (unsigned)p.H;
+      dma16(ok ? xsrc + prel[u] : zsrc, live ? base + 16384 + wl * 1024 : lds_dump);
     }
   };
 

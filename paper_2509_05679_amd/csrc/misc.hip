@@ -232,45 +232,106 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float* logits, co
 }
 
 // ------------------------------------------------------------------ update
-// block_map[2*blk] = descriptor index, block_map[2*blk+1] = block within the descriptor.
-// g = (1/W) * sum over splits (fixed order); v = mu*v + g; w -= lr*v (or lr*g)
+// block_map[2*blk] = descriptor index, block_map[2*blk+1] = block within the descriptor
+// (1024 elements per block). Eight lanes share four consecutive elements: lane q sums the
+// splits q, q+8, q+16, ... in increasing order, then a fixed butterfly over the eight lanes
+// adds the partial sums, so the result is bit-reproducible whatever the split count while
+// eight split streams are read in parallel. g = sum/W; v = mu*v + g; w -= lr*v (or lr*g).
 template <typename T>
 __global__ __launch_bounds__(256) void update_kernel(const UpdateDesc* descs, const int* block_map, float invW, float lr, float mu) {
   const UpdateDesc d = descs[block_map[2 * blockIdx.x]];
-  const long long base = (long long)block_map[2 * blockIdx.x + 1] * 1024 + threadIdx.x * 4;
-  if (base >= d.n) return;
-  if (base + 4 <= d.n) {
-    // fixed summation order (bit-reproducible): eight interleaved running sums keep
-    // eight loads in flight, then a fixed tree combines them
-    float4 a[8];
+  const long long blk0 = (long long)block_map[2 * blockIdx.x + 1] * 1024;
+  if (d.nsplit > 32) {
+    // many splits: one thread per four elements walks all splits (fully coalesced rows,
+    // eight loads in flight), fixed tree at the end
+    const long long base = blk0 + threadIdx.x * 4;
+    if (base >= d.n) return;
+    const bool vec = base + 4 <= d.n;
+    float4 s8[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    int j = 0;
-    for (; j + 8 <= d.nsplit; j += 8) {
+    for (int u = 0; u < 8; ++u) s8[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < d.nsplit; j += 8) {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const float4 q = *(const float4*)(d.partial + (size_t)(j + u) * d.pstride + base);
-        a[u].x += q.x; a[u].y += q.y; a[u].z += q.z; a[u].w += q.w;
+        if (j + u < d.nsplit) {
+          const float* src = d.partial + (size_t)(j + u) * d.pstride + base;
+          if (vec) {
+            const float4 t = *(const float4*)src;
+            s8[u].x += t.x; s8[u].y += t.y; s8[u].z += t.z; s8[u].w += t.w;
+          } else {
+            s8[u].x += src[0];
+            if (base + 1 < d.n) s8[u].y += src[1];
+            if (base + 2 < d.n) s8[u].z += src[2];
+          }
+        }
       }
-    }
-    for (int u = 0; j < d.nsplit; ++j, ++u) {
-      const float4 q = *(const float4*)(d.partial + (size_t)j * d.pstride + base);
-      a[u].x += q.x; a[u].y += q.y; a[u].z += q.z; a[u].w += q.w;
     }
 #pragma unroll
     for (int w = 4; w > 0; w >>= 1)
 #pragma unroll
-      for (int u = 0; u < w; ++u) { a[u].x += a[u + w].x; a[u].y += a[u + w].y; a[u].z += a[u + w].z; a[u].w += a[u + w].w; }
-    float4 g = a[0];
-    g.x *= invW; g.y *= invW; g.z *= invW; g.w *= invW;
+      for (int u = 0; u < w; ++u) { s8[u].x += s8[u + w].x; s8[u].y += s8[u + w].y; s8[u].z += s8[u + w].z; s8[u].w += s8[u + w].w; }
+    float g[4] = {s8[0].x * invW, s8[0].y * invW, s8[0].z * invW, s8[0].w * invW};
+    for (int e = 0; e < 4 && base + e < d.n; ++e) {
+      const long long i = base + e;
+      float w = d.master[i];
+      float gg = g[e];
+      if (d.momentum) { const float v = mu * d.momentum[i] + gg; d.momentum[i] = v; gg = v; }
+      w -= lr * gg;
+      d.master[i] = w;
+      if (d.work) {
+        if (sizeof(T) == 2) ((uint16_t*)d.work)[i] = f2bf(w);
+        else ((float*)d.work)[i] = w;
+      }
+    }
+    return;
+  }
+  const int q = threadIdx.x & 7;            // split lane
+  const int grp = threadIdx.x >> 3;         // 32 element groups of 4 per pass, 8 passes per block
+  float4 a[8];
+#pragma unroll
+  for (int pass = 0; pass < 8; ++pass) a[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
+  // eight independent loads in flight per split; an element group past the end (or a ragged
+  // tail that cannot be read as one vector) is summed by the scalar path below
+  for (int j = q; j < d.nsplit; j += 8) {
+    const float* src = d.partial + (size_t)j * d.pstride + blk0 + grp * 4;
+#pragma unroll
+    for (int pass = 0; pass < 8; ++pass) {
+      const long long base = blk0 + (pass * 32 + grp) * 4;
+      if (base + 4 <= d.n) {
+        const float4 t = *(const float4*)(src + pass * 128);
+        a[pass].x += t.x; a[pass].y += t.y; a[pass].z += t.z; a[pass].w += t.w;
+      } else if (base < d.n) {
+        a[pass].x += src[pass * 128];
+        if (base + 1 < d.n) a[pass].y += src[pass * 128 + 1];
+        if (base + 2 < d.n) a[pass].z += src[pass * 128 + 2];
+      }
+    }
+  }
+#pragma unroll
+  for (int pass = 0; pass < 8; ++pass) {
+    float4& s4 = a[pass];
+#pragma unroll
+    for (int w = 4; w > 0; w >>= 1) {  // fixed butterfly: lanes q and q^w hold the same value afterwards
+      s4.x += __shfl_xor(s4.x, w, 8); s4.y += __shfl_xor(s4.y, w, 8); s4.z += __shfl_xor(s4.z, w, 8); s4.w += __shfl_xor(s4.w, w, 8);
+    }
+  }
+  // lane q finishes pass q of its group: all 256 threads write
+  float4 mine = a[0];
+#pragma unroll
+  for (int pass = 1; pass < 8; ++pass)
+    if (q == pass) mine = a[pass];
+  const long long base = blk0 + (q * 32 + grp) * 4;
+  if (base >= d.n) return;
+  float g[4] = {mine.x * invW, mine.y * invW, mine.z * invW, mine.w * invW};
+  if (base + 4 <= d.n) {
     float4 w = *(const float4*)(d.master + base);
     if (d.momentum) {
       float4 v = *(const float4*)(d.momentum + base);
-      v.x = mu * v.x + g.x; v.y = mu * v.y + g.y; v.z = mu * v.z + g.z; v.w = mu * v.w + g.w;
+      v.x = mu * v.x + g[0]; v.y = mu * v.y + g[1]; v.z = mu * v.z + g[2]; v.w = mu * v.w + g[3];
       *(float4*)(d.momentum + base) = v;
-      g = v;
+      g[0] = v.x; g[1] = v.y; g[2] = v.z; g[3] = v.w;
     }
-    w.x -= lr * g.x; w.y -= lr * g.y; w.z -= lr * g.z; w.w -= lr * g.w;
+    w.x -= lr * g[0]; w.y -= lr * g[1]; w.z -= lr * g[2]; w.w -= lr * g[3];
     *(float4*)(d.master + base) = w;
     if (d.work) {
       if (sizeof(T) == 2) {
@@ -284,12 +345,10 @@ __global__ __launch_bounds__(256) void update_kernel(const UpdateDesc* descs, co
     }
   } else {
     for (long long i = base; i < d.n; ++i) {
-      float g = 0.f;
-      for (int j = 0; j < d.nsplit; ++j) g += d.partial[(size_t)j * d.pstride + i];
-      g *= invW;
       float w = d.master[i];
-      if (d.momentum) { float v = mu * d.momentum[i] + g; d.momentum[i] = v; g = v; }
-      w -= lr * g;
+      float gg = g[i - base];
+      if (d.momentum) { const float v = mu * d.momentum[i] + gg; d.momentum[i] = v; gg = v; }
+      w -= lr * gg;
       d.master[i] = w;
       if (d.work) {
         if (sizeof(T) == 2) ((uint16_t*)d.work)[i] = f2bf(w);
