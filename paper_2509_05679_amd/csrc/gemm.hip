@@ -11,6 +11,8 @@
 namespace dds {
 namespace {
 
+#define DDS_LDS_AS __attribute__((address_space(3)))
+
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 
@@ -65,6 +67,20 @@ __device__ __forceinline__ void mma_step(const char* As, const char* Bs, int lan
   }
 }
 
+// LDS loads through an explicit address-space pointer (HIP's vector classes cannot be
+// referenced through one, so native vector types carry the bits)
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+template <typename R> __device__ __forceinline__ R lds_load(const char DDS_LDS_AS* p);
+template <> __device__ __forceinline__ uint4 lds_load<uint4>(const char DDS_LDS_AS* p) {
+  const u32x4_t v = *(const u32x4_t DDS_LDS_AS*)p;
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+template <> __device__ __forceinline__ uint2 lds_load<uint2>(const char DDS_LDS_AS* p) {
+  const u32x2_t v = *(const u32x2_t DDS_LDS_AS*)p;
+  return make_uint2(v.x, v.y);
+}
+
 // Four consecutive output channels of one pixel: v = alpha*(acc+bias) (+res) (relu) (mask),
 // moved with one 8-byte (bf16) or 16-byte (fp32) access per operand. n is a multiple of 4.
 template <typename T> __device__ __forceinline__ void load4(const void* p, size_t i, float* v);
@@ -111,6 +127,17 @@ __device__ __forceinline__ void unpack4(const uint2& t, float* v) {
   v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
 }
 
+// x > 0 decided on the stored bits (no conversion): fp32 as is; a packed bf16 pair w holds
+// lo in bits 0-15 and hi in bits 16-31: hi > 0 <=> (int)w >= 0x10000, lo > 0 <=> (int)(w << 16) >= 0x10000
+__device__ __forceinline__ void positive4(const uint4& t, bool* pos) {
+  pos[0] = __uint_as_float(t.x) > 0.f; pos[1] = __uint_as_float(t.y) > 0.f;
+  pos[2] = __uint_as_float(t.z) > 0.f; pos[3] = __uint_as_float(t.w) > 0.f;
+}
+__device__ __forceinline__ void positive4(const uint2& t, bool* pos) {
+  pos[0] = (int)(t.x << 16) >= 0x10000; pos[1] = (int)t.x >= 0x10000;
+  pos[2] = (int)(t.y << 16) >= 0x10000; pos[3] = (int)t.y >= 0x10000;
+}
+
 // bias values of this lane's channel groups (zero past Nout), read once per kernel
 template <int NJ>
 __device__ __forceinline__ void load_bias_groups(const ConvParams& p, int nb, float (&bias)[NJ][4][4]) {
@@ -133,8 +160,8 @@ __device__ __forceinline__ void load_bias_groups(const ConvParams& p, int nb, fl
 template <typename T, int NJ, int NI>
 __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_t (&acc)[NJ][NI], int i, bool valid,
                                               size_t pix, int nb, const float (&bias)[NJ][4][4],
-                                              const char* res_lds = nullptr, const char* mask_lds = nullptr,
-                                              int tile_row = 0, int row_bytes = 0, int nloc0 = 0) {
+                                              const char DDS_LDS_AS* lds = nullptr, int res_off = -1, int mask_off = -1,
+                                              int tile_row = 0, int row_bytes = 0, int nloc0 = 0, int ab_off = -1) {
   typedef typename Raw4<T>::type raw_t;
   size_t o[NJ][4];
   bool ok[NJ][4];
@@ -148,31 +175,40 @@ __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_
       ok[j][g] = valid && n < p.ldy;
       o[j][g] = ok[j][g] ? pix * p.ldy + n : 0;
     }
-  auto lds_at = [&](const char* base, int j, int g) {
+  // explicit LDS address space: a generic pointer would turn these into flat loads, which
+  // also count as vector-memory operations and would wait for every earlier global store
+  auto lds_at = [&](int base_off, int j, int g) {
     const int bytecol = (nloc0 + 32 * j + 8 * g) * (int)sizeof(T);
-    return base + tile_row * row_bytes + ((((bytecol >> 4) ^ tile_row) & ncolm) << 4) + (bytecol & 15);
+    return lds + base_off + tile_row * row_bytes + ((((bytecol >> 4) ^ tile_row) & ncolm) << 4) + (bytecol & 15);
   };
   if (p.res) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        r[j][g] = res_lds ? *(const raw_t*)lds_at(res_lds, j, g) : *(const raw_t*)((const T*)p.res + o[j][g]);
+        r[j][g] = res_off >= 0 ? lds_load<raw_t>(lds_at(res_off, j, g)) : *(const raw_t*)((const T*)p.res + o[j][g]);
   }
   if (p.mask) {
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        mk[j][g] = mask_lds ? *(const raw_t*)lds_at(mask_lds, j, g) : *(const raw_t*)((const T*)p.mask + o[j][g]);
+        mk[j][g] = mask_off >= 0 ? lds_load<raw_t>(lds_at(mask_off, j, g)) : *(const raw_t*)((const T*)p.mask + o[j][g]);
   }
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       float v[4];
+      if (ab_off >= 0) {  // alpha * bias staged in LDS: no global load (and no wait on earlier stores) in this loop
+        const uint4 abr = lds_load<uint4>(lds + ab_off + (nloc0 + 32 * j + 8 * g) * 4);
+        const float4 ab = make_float4(__uint_as_float(abr.x), __uint_as_float(abr.y), __uint_as_float(abr.z), __uint_as_float(abr.w));
+        v[0] = fmaf(p.alpha, acc[j][i][4 * g + 0], ab.x); v[1] = fmaf(p.alpha, acc[j][i][4 * g + 1], ab.y);
+        v[2] = fmaf(p.alpha, acc[j][i][4 * g + 2], ab.z); v[3] = fmaf(p.alpha, acc[j][i][4 * g + 3], ab.w);
+      } else {
 #pragma unroll
-      for (int q = 0; q < 4; ++q) v[q] = p.alpha * (acc[j][i][4 * g + q] + bias[j][g][q]);
+        for (int q = 0; q < 4; ++q) v[q] = p.alpha * (acc[j][i][4 * g + q] + bias[j][g][q]);
+      }
       if (p.res) {
         float t[4];
         unpack4(r[j][g], t);
@@ -181,13 +217,13 @@ __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_
       }
       if (p.relu) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = v[q] > 0.f ? v[q] : 0.f;
+        for (int q = 0; q < 4; ++q) v[q] = __builtin_amdgcn_fmed3f(v[q], 0.f, __builtin_inff());  // one instruction; NaN -> 0
       }
       if (p.mask) {
-        float t[4];
-        unpack4(mk[j][g], t);
+        bool pos[4];
+        positive4(mk[j][g], pos);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = t[q] > 0.f ? v[q] : 0.f;
+        for (int q = 0; q < 4; ++q) v[q] = pos[q] ? v[q] : 0.f;
       }
       if (ok[j][g]) {
         if (p.out_f32) store4<float>(p.y, o[j][g], v);
@@ -497,7 +533,6 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(ConvParams p, Halo
 // LDS rows are 128 unpadded bytes; the 16-byte column c of row r lives at column
 // c ^ (r & 7), which keeps eight consecutive rows on distinct banks for the MFMA
 // fragment reads; the swizzle is applied by choosing which global column a lane fetches.
-#define DDS_LDS_AS __attribute__((address_space(3)))
 __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_base_uniform) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base_uniform) : "memory");
 }
@@ -675,13 +710,18 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   constexpr int NCOL = ROWB / 16;      // 16-byte columns per row
   constexpr int RPF = 64 / NCOL;       // rows per wave fill
   constexpr int FPW = BM / RPF / 4;    // fills per wave
-  const char* res_lds = nullptr;
-  const char* mask_lds = nullptr;
+  int res_off = -1, mask_off = -1;
+  const int ab_off = (int)(lds_dump - lds0);  // the dump block now holds alpha * bias of this tile's channels
+  float* ab_lds = (float*)(smem + ab_off);
+  wg_barrier();
+  if (tid < BN) {
+    const int n = n0 + tid;
+    ab_lds[tid] = (p.bias != nullptr && n < p.Nout) ? p.alpha * p.bias[n] : 0.f;
+  }
   if (p.res || p.mask) {
-    wg_barrier();
     int region = 0;
-    auto stage_tile = [&](const void* src_tensor) -> const char* {
-      if ((region + 1) * BM * ROWB > dg.smem_bytes) return nullptr;
+    auto stage_tile = [&](const void* src_tensor) -> int {
+      if ((region + 1) * BM * ROWB > dg.smem_bytes - 1024) return -1;
       const int rbase = region * BM * ROWB;
 #pragma unroll
       for (int u = 0; u < FPW; ++u) {
@@ -697,24 +737,24 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
         dma16(src, lds0 + rbase + f * 1024);
       }
       ++region;
-      return smem + rbase;
+      return rbase;
     };
-    if (p.mask) mask_lds = stage_tile(p.mask);
-    if (p.res) res_lds = stage_tile(p.res);
+    if (p.mask) mask_off = stage_tile(p.mask);
+    if (p.res) res_off = stage_tile(p.res);
     wait_vm<0>();
-    wg_barrier();
   }
+  __syncthreads();  // also orders the plain LDS stores of alpha * bias
 
   const int nb = n0 + wave_n * WN + 4 * (lane >> 5);
-  float bias[NJ][4][4];
-  load_bias_groups<NJ>(p, nb, bias);
+  float bias[NJ][4][4] = {};
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int m = wave_m * WM + i * 32 + (lane & 31);
     const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
     const int gi = img0 + im;
     const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
-    epilogue_tile<T, NJ, NI>(p, acc, i, gi < p.Nimg, pix, nb, bias, res_lds, mask_lds, m, ROWB, wave_n * WN + 4 * (lane >> 5));
+    epilogue_tile<T, NJ, NI>(p, acc, i, gi < p.Nimg, pix, nb, bias, (const char DDS_LDS_AS*)smem, res_off, mask_off, m, ROWB,
+                             wave_n * WN + 4 * (lane >> 5), ab_off);
   }
 }
 
