@@ -108,3 +108,69 @@ def test_cfg2_resnet18_reduced_batch_bf16():
 def test_cfg2_resnet18_reduced_batch_fp32_arithmetic():
     wl = workload("cfg2_resnet18", B=3, precision="f32")
     _compare(wl, seed=1, T=2 * (wl.K - 1) + 4)
+
+
+def test_cfg3_resnet56_reduced_batch_bf16():
+    # K=8 modules, W=8 replicas, narrow channels (16/32/64): the generic implicit-GEMM path and ring
+    # depths up to 15; per-replica batch 2 keeps the oracle leg short
+    wl = workload("cfg3_resnet56", B=2)
+    _compare(wl, seed=0, T=2 * (wl.K - 1) + 6)
+
+
+def test_cfg4_resnet34w_reduced_batch_bf16():
+    wl = workload("cfg4_resnet34w", B=1, W=4)
+    _compare(wl, seed=0, T=2 * (wl.K - 1) + 3)
+
+
+def test_cfg2_full_size_first_updates_against_sampled_oracle():
+    """Benchmark shape (W*B = 512, the launch configuration bench.py times). The oracle cannot run the
+    whole pipeline at this size in seconds, so it computes what is checkable one piece at a time: the
+    loss of batch 0 at the initial weights and the last module's first update (iteration K-1), which
+    needs one full-batch forward and the last module's backward only."""
+    import torch
+    from dds_inputs import make_batch, make_params
+    from oracle import network as N
+    import paper_2509_05679_amd as P
+    wl = workload("cfg2_resnet18")
+    seed = 3
+    K = wl.K
+    spec = P.Spec.from_workload(wl)
+    tr = P.Trainer(spec, wl.W)
+    init = make_params(wl, seed)
+    for k0 in range(K):
+        tr.dds_set_params(k0, init[k0])
+    for t in range(K):
+        xs = [torch.from_numpy(make_batch(wl, seed, t, s)[0]).cuda() for s in range(wl.W)]
+        ys = [torch.from_numpy(make_batch(wl, seed, t, s)[1]).cuda() for s in range(wl.W)]
+        tr.dds_step(xs, ys)
+    torch.cuda.synchronize()
+    loss_hip = tr.dds_get_loss()
+    last_hip = tr.dds_get_params(K - 1)
+    first_hip = tr.dds_get_params(0)
+    tr.close()
+    # oracle: forward of batch 0 through every module at the initial weights, replica by replica
+    DT = torch.float64
+    mods = [[torch.as_tensor(p, dtype=DT) for p in m] for m in init]
+    losses, grads = [], None
+    for s in range(wl.W):
+        x, y = make_batch(wl, seed, 0, s)
+        h = torch.as_tensor(x, dtype=DT)
+        for k0 in range(K - 1):
+            h, _, _ = N.forward(wl.ops[wl.bounds[k0]:wl.bounds[k0 + 1]], mods[k0], h)
+        ops = wl.ops[wl.bounds[K - 1]:]
+        dlog, saved, loss = N.forward(ops, mods[K - 1], h, torch.as_tensor(y, dtype=torch.int64))
+        _, g = N.backward(ops, mods[K - 1], saved, dlog, need_dx=True)
+        losses.append(float(loss))
+        grads = g if grads is None else [a + b for a, b in zip(grads, g)]
+    want_loss = float(np.mean(losses))
+    assert abs(loss_hip - want_loss) <= 2e-2 * abs(want_loss), (loss_hip, want_loss)
+    want = np.concatenate([(p - wl.lr * g / wl.W).numpy().ravel() for p, g in zip(mods[K - 1], grads)])
+    init_last = np.concatenate([p.numpy().ravel() for p in mods[K - 1]])
+    from parity import tensor_slices
+    for name, sl in tensor_slices(wl, K - 1):
+        du = np.linalg.norm(want[sl] - init_last[sl])
+        err = np.linalg.norm(last_hip[sl] - want[sl])
+        print(f"[parity] full-size cfg2 module {K-1} {name}: update-rel {err / du:.3e}", flush=True)
+        assert err <= UPDATE_TOL["bf16"] * du, name
+    # module 0 has not received a gradient yet (first one at iteration 2(K-1)): bit-exact initial weights
+    assert np.array_equal(first_hip, np.concatenate([p.ravel() for p in init[0]]))
