@@ -23,7 +23,9 @@ PEAK = {"bf16": 2500.0, "f32": 157.3}  # dense MFMA TFLOP/s of MI355X
 
 def hip_event_timer():
     """HIP events through libamdhip64 (works on any stream, unlike torch.cuda.Event)."""
-    hip = ctypes.CDLL("libamdhip64.so")
+    import torch
+    bundled = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    hip = ctypes.CDLL(bundled if os.path.exists(bundled) else "libamdhip64.so")  # the runtime torch and libdds use
     hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
     hip.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
     hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]

@@ -51,6 +51,10 @@ class DdsError(RuntimeError):
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    # The arena and the streams handed to the library come from PyTorch, so both must talk to
+    # one HIP runtime: load PyTorch's first, libdds.so then binds to it by soname. (Loaded the
+    # other way round the process holds two runtimes and the second finds no device.)
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float)
     lib.dds_schedule.argtypes = [C.c_int, C.POINTER(C.c_int), C.c_int64, i32p]

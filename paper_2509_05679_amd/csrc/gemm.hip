@@ -530,9 +530,14 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(ConvParams p, Halo
 // compiler does not model these copies, so their completion is counted by hand: loads
 // retire in order, every stage issues a fixed number per lane, and each stage waits
 // until only the younger ones are outstanding, then crosses one workgroup barrier.
-// LDS rows are 128 unpadded bytes; the 16-byte column c of row r lives at column
-// c ^ (r & 7), which keeps eight consecutive rows on distinct banks for the MFMA
-// fragment reads; the swizzle is applied by choosing which global column a lane fetches.
+// LDS rows are KB unpadded bytes; the 16-byte column c of a row lives at column c ^ f(row),
+// applied by choosing which global column a lane fetches. A 16-byte-per-lane LDS read is
+// served 16 lanes per cycle from 64 four-byte banks, and the 16 lanes of one cycle are the
+// four-lane quads q = lane/4 of a 32-lane half whose index has even (or odd) bit parity:
+// {0,3,5,6} and {1,2,4,7} (measured). f is chosen so that each such set reads 16 different
+// 16-byte bank groups: weight rows (consecutive across lanes) use f = (row * KB / 256) mod
+// (KB/16); patch rows use bits of the patch coordinates (see patch_swizzle), and the pixels
+// of a 32-pixel fragment are dealt to lanes so that one cycle's lanes hold 16 consecutive ones.
 __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_base_uniform) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base_uniform) : "memory");
 }
@@ -553,6 +558,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   constexpr int CPR = KB / 16;         // 16-byte columns per row
   constexpr int WL = BN / FROWS / 4;   // weight fills per lane per stage
   constexpr int NKS = KB / 32;         // MFMA k-steps per stage
+  constexpr int FB = KB == 128 ? 3 : 2;   // swizzle bits = log2(CPR)
+  constexpr int RPL = KB == 128 ? 1 : 2;  // log2(rows per 256 bytes of LDS)
+  static_assert(KB == 64 || KB == 128, "row depth");
   static_assert(WL >= 1, "weight tile smaller than one fill per wave");
   constexpr int NI = WM / 32, NJ = WN / 32;
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
@@ -578,6 +586,13 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   const int TWm = (1 << g.tw_log) - 1, THm = (1 << g.th_log) - 1;
   const int nchunks = (p.Cx * ES) / KB;
   const size_t pixbytes = (size_t)p.Cx * ES;
+  // Swizzle of the patch row at patch coordinates (xx, yy). One LDS cycle reads a 16-pixel
+  // run of the tile: 16 x 1, 8 x 2 or 4 x 4 pixels, shifted by the tap. The low RPL bits of x
+  // already spread a run over the rows of one 256-byte bank line; f takes the next bits of x
+  // that vary inside the run and fills up with low bits of y.
+  const int sw_nx = min(FB, max(0, g.tw_log - RPL));
+  const int sw_mx = (1 << sw_nx) - 1, sw_my = (1 << (FB - sw_nx)) - 1;
+  auto patch_swizzle = [&](int xx, int yy) { return ((xx >> RPL) & sw_mx) | ((yy & sw_my) << sw_nx); };
 
   // pixel-offset table of the patch rows: pixel index in the gathered tensor, or -1 (zero row)
   for (int row = tid; row < prow; row += 256) {
@@ -586,25 +601,27 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
       const int im = row / g.PP, rem = row - im * g.PP;
       const int yy = rem / g.PW, xx = rem - yy * g.PW;
       const int gi = img0 + im, gh = h0 + yy - 1, gw = w0 + xx - 1;
-      if (gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W) v = (gi * p.H + gh) * p.W + gw;
+      if (gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W)
+        v = ((gi * p.H + gh) * p.W + gw) * CPR + patch_swizzle(xx, yy);
     }
     tab[row] = v;
   }
   __syncthreads();
 
-  // column swizzle of a row: eight (KB=128) or four (KB=64) consecutive rows land on distinct banks
-  auto swz = [](int r) { return KB == 128 ? (r & 7) : ((r >> 1) & 3); };
+  // column swizzle of a weight row (rows are consecutive across lanes, fills start at multiples of FROWS rows)
+  auto swz = [](int r) { return (r >> RPL) & (CPR - 1); };
   const int l8 = lane / CPR;  // row inside a fill
-  const int c16 = ((lane % CPR) ^ swz(l8)) * 16;  // global 16-byte column this lane fetches (fills start at multiples of FROWS rows)
-  const char* zsrc = (const char*)p.zeros + c16;
+  const int c16 = ((lane % CPR) ^ swz(l8 + (wave & 1) * FROWS)) * 16;  // global 16-byte column of the weight row this lane fetches
+  const int pcol = lane % CPR;
+  const char* zsrc = (const char*)p.zeros;
   const int pw_total = prow / FROWS;  // wave fills in a patch
   const uint32_t lds_dump = lds_wring + 3 * (BN * KB);  // 1 KiB that absorbs surplus fills
   const int tab_lane = l8 * 4;
   auto fill_patch = [&](int j, int chunk, int buf) {  // j-th fill of this wave; surplus ones go to the dump block
     const int wl = wave + 4 * j;
     const bool live = wl < pw_total;  // wave-uniform
-    const int off = *(const int*)((const char*)tab + (live ? wl * (FROWS * 4) : 0) + tab_lane);
-    const char* src = off >= 0 ? (const char*)p.x + (size_t)off * pixbytes + (size_t)chunk * KB + c16 : zsrc;
+    const int off = *(const int*)((const char*)tab + (live ? wl * (FROWS * 4) : 0) + tab_lane);  // pixel * CPR + f, or -1
+    const char* src = off >= 0 ? (const char*)p.x + (size_t)(off >> FB) * pixbytes + (size_t)chunk * KB + ((pcol ^ (off & (CPR - 1))) << 4) : zsrc;
     dma16(src, live ? lds_pbuf + buf * pbuf_bytes + wl * 1024 : lds_dump);
   };
   const char* wsrc[WL];
@@ -623,12 +640,16 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   };
 
   // fragment addressing
-  int arow[NI];
+  // pixel of the 32-pixel fragment held by this lane: quads {0,3,5,6} -> pixels 0..15, {1,2,4,7} -> 16..31
+  const int lq = (lane >> 2) & 7;
+  const int lpix = ((__builtin_popcount(lq) & 1) << 4) | ((lq >> 1) << 2) | (lane & 3);
+  int arow[NI], axy[NI];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    const int m = wave_m * WM + i * 32 + (lane & 31);
+    const int m = wave_m * WM + i * 32 + lpix;
     const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
     arow[i] = im * g.PP + y * g.PW + x;
+    axy[i] = x | (y << 8);
   }
   const int half = lane >> 5;
   int boff[NJ][NKS];
@@ -659,11 +680,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     int aaddr[NI], aswz[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      int base = arow[i];
-      asm volatile("" : "+v"(base));  // keep the per-tap addresses from being hoisted (and spilled) for all nine taps
+      int base = arow[i], xy = axy[i];
+      asm volatile("" : "+v"(base), "+v"(xy));  // keep the per-tap addresses from being hoisted (and spilled) for all nine taps
       const int r = base + tapoff;
       aaddr[i] = r * KB;
-      aswz[i] = swz(r) << 4;
+      aswz[i] = patch_swizzle((xy & 255) + (g.flip ? 2 - tap_s : tap_s), (xy >> 8) + (g.flip ? 2 - tap_r : tap_r)) << 4;
     }
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
@@ -749,7 +770,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   float bias[NJ][4][4] = {};
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
-    const int m = wave_m * WM + i * 32 + (lane & 31);
+    const int m = wave_m * WM + i * 32 + lpix;
     const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
     const int gi = img0 + im;
     const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
