@@ -144,7 +144,7 @@ struct dds_ctx {
   int label_depth = 0;
   int32_t* labels = nullptr;  // [label_depth][N]
   float* loss = nullptr;      // [W]
-  char* zeros = nullptr;      // 256 zero bytes
+  char* zeros = nullptr;      // kZeroBytes zero bytes
   int64_t t = 0;
   bool have_loss = false;
   hipEvent_t fork = nullptr;
@@ -461,7 +461,7 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
   c.label_depth = c.K + 2 * c.d[c.K - 1];
   c.labels = (int32_t*)A.take(sizeof(int32_t) * c.N * c.label_depth);
   c.loss = (float*)A.take(sizeof(float) * c.W);
-  c.zeros = A.take(256);
+  c.zeros = A.take(kZeroBytes);
   (void)sp;
   return DDS_OK;
 }

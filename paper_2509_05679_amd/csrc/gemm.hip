@@ -541,6 +541,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(ConvParams p, Halo
 __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_base_uniform) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base_uniform) : "memory");
 }
+// Same copy with the address split into a wave-uniform 64-bit base (SGPR pair) and a per-lane
+// unsigned 32-bit byte offset: the per-copy address arithmetic stays on the scalar unit.
+__device__ __forceinline__ void dma16s(const void* gbase_uniform, uint32_t goff, uint32_t lds_base_uniform) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(goff), "s"(gbase_uniform), "s"(lds_base_uniform) : "memory");
+}
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
@@ -611,47 +616,62 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   // column swizzle of a weight row (rows are consecutive across lanes, fills start at multiples of FROWS rows)
   auto swz = [](int r) { return (r >> RPL) & (CPR - 1); };
   const int l8 = lane / CPR;  // row inside a fill
-  const int c16 = ((lane % CPR) ^ swz(l8 + (wave & 1) * FROWS)) * 16;  // global 16-byte column of the weight row this lane fetches
   const int pcol = lane % CPR;
-  const char* zsrc = (const char*)p.zeros;
+  const char* zsrc = (const char*)p.zeros + pcol * 16;  // the zero block is at least one pixel row long
   const int pw_total = prow / FROWS;  // wave fills in a patch
   const uint32_t lds_dump = lds_wring + 3 * (BN * KB);  // 1 KiB that absorbs surplus fills
-  const int tab_lane = l8 * 4;
-  auto fill_patch = [&](int j, int chunk, int buf) {  // j-th fill of this wave; surplus ones go to the dump block
+  // Source of this lane's 16 bytes in the j-th patch fill of this wave, for channel chunk 0.
+  // Rows outside the image and surplus fills read the zero block.
+  auto patch_src = [&](int j) -> const char* {
     const int wl = wave + 4 * j;
     const bool live = wl < pw_total;  // wave-uniform
-    const int off = *(const int*)((const char*)tab + (live ? wl * (FROWS * 4) : 0) + tab_lane);  // pixel * CPR + f, or -1
-    const char* src = off >= 0 ? (const char*)p.x + (size_t)(off >> FB) * pixbytes + (size_t)chunk * KB + ((pcol ^ (off & (CPR - 1))) << 4) : zsrc;
-    dma16(src, live ? lds_pbuf + buf * pbuf_bytes + wl * 1024 : lds_dump);
+    const int off = tab[(live ? wl * FROWS : 0) + l8];  // pixel * CPR + f, or -1
+    return live && off >= 0 ? (const char*)p.x + (size_t)(off >> FB) * pixbytes + ((pcol ^ (off & (CPR - 1))) << 4) : zsrc;
   };
-  const char* wsrc[WL];
-  bool wok[WL];
+  auto patch_dst = [&](int j, int buf) {
+    const int wl = wave + 4 * j;
+    return wl < pw_total ? lds_pbuf + buf * pbuf_bytes + wl * 1024 : lds_dump;
+  };
+  constexpr int NPF = 7 * PS;  // patch fills per wave and chunk issued inside the loop
+  const char* psrc[NPF > 0 ? NPF : 1];
+#pragma unroll
+  for (int j = 0; j < NPF; ++j) psrc[j] = patch_src(j);
+  // weight rows: byte offset of this lane's 16 bytes inside the weight tensor at tap 0, chunk 0.
+  // Rows past Nout repeat the last one: their output columns lie past ldy == Nout and are never stored.
+  uint32_t wvo[WL];
 #pragma unroll
   for (int u = 0; u < WL; ++u) {
     const int gn = n0 + (wave + 4 * u) * FROWS + l8;
-    wok[u] = gn < p.Nout;
-    wsrc[u] = (const char*)p.w + (size_t)(wok[u] ? gn : 0) * 9 * pixbytes + c16;
+    const int c16 = (pcol ^ swz(l8 + (wave & 1) * FROWS)) * 16;
+    wvo[u] = (uint32_t)(gn < p.Nout ? gn : p.Nout - 1) * (uint32_t)(9 * pixbytes) + c16;
   }
   auto fill_w = [&](int chunk, int tap, int slot) {
-    const size_t off = (size_t)tap * pixbytes + (size_t)chunk * KB;
+    const char* base = (const char*)p.w + (size_t)tap * pixbytes + (size_t)chunk * KB;  // wave-uniform
 #pragma unroll
-    for (int u = 0; u < WL; ++u)
-      dma16(wok[u] ? wsrc[u] + off : zsrc, lds_wring + slot * (BN * KB) + (wave + 4 * u) * 1024);
+    for (int u = 0; u < WL; ++u) dma16s(base, wvo[u], lds_wring + slot * (BN * KB) + (wave + 4 * u) * 1024);
   };
 
   // fragment addressing
   // pixel of the 32-pixel fragment held by this lane: quads {0,3,5,6} -> pixels 0..15, {1,2,4,7} -> 16..31
   const int lq = (lane >> 2) & 7;
   const int lpix = ((__builtin_popcount(lq) & 1) << 4) | ((lq >> 1) << 2) | (lane & 3);
-  int arow[NI], axy[NI];
+  const int half = lane >> 5;
+  // Patch operand: LDS byte offset of a fragment row = row * KB + (((2 ks + half) ^ f) << 4) with
+  // f = fx(x + tap_s) | fy(y + tap_r). Per lane and tap coordinate the swizzle bits are kept in
+  // registers (sx also carries half), so a stage needs one add, one xor-add and one xor per k-step.
+  int rowb[NI], sx[NI][3], sy[NI][3];
 #pragma unroll
   for (int i = 0; i < NI; ++i) {
     const int m = wave_m * WM + i * 32 + lpix;
     const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
-    arow[i] = im * g.PP + y * g.PW + x;
-    axy[i] = x | (y << 8);
+    rowb[i] = (im * g.PP + y * g.PW + x) * KB;
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+      const int tt = g.flip ? 2 - t : t;
+      sx[i][t] = ((patch_swizzle(x + tt, 0)) ^ half) << 4;
+      sy[i][t] = patch_swizzle(0, y + tt) << 4;
+    }
   }
-  const int half = lane >> 5;
   int boff[NJ][NKS];
 #pragma unroll
   for (int j = 0; j < NJ; ++j) {
@@ -669,28 +689,27 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
   // prologue: whole first patch, then the weight tiles of stages 0 and 1
-  for (int j = 0; wave + 4 * j < pw_total; ++j) fill_patch(j, 0, 0);
+  for (int j = 0; wave + 4 * j < pw_total; ++j) dma16(patch_src(j), patch_dst(j, 0));
   fill_w(0, 0, 0);
   fill_w(0, 1, 1);
 
+  const int pbuf_off = dg.tab_bytes;
   auto compute = [&](int chunk, int tap_r, int tap_s, int slot) {
     const int tapoff = (g.flip ? 2 - tap_r : tap_r) * g.PW + (g.flip ? 2 - tap_s : tap_s);
-    const char* pb = pbuf + (PS > 0 ? (chunk & 1) * pbuf_bytes : 0);
+    const int sbase = pbuf_off + (PS > 0 ? (chunk & 1) * pbuf_bytes : 0) + tapoff * KB;  // wave-uniform
     const char* wb = wring + slot * (BN * KB);
-    int aaddr[NI], aswz[NI];
+    int a0[NI];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      int base = arow[i], xy = axy[i];
-      asm volatile("" : "+v"(base), "+v"(xy));  // keep the per-tap addresses from being hoisted (and spilled) for all nine taps
-      const int r = base + tapoff;
-      aaddr[i] = r * KB;
-      aswz[i] = patch_swizzle((xy & 255) + (g.flip ? 2 - tap_s : tap_s), (xy >> 8) + (g.flip ? 2 - tap_r : tap_r)) << 4;
+      int rb = rowb[i];
+      asm volatile("" : "+v"(rb));  // keeps the nine taps' addresses from being precomputed (and spilled)
+      a0[i] = (sx[i][tap_s] ^ sy[i][tap_r]) + (rb + sbase);
     }
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) {
       uint4 a[NI], b[NJ];
 #pragma unroll
-      for (int i = 0; i < NI; ++i) a[i] = *(const uint4*)(pb + aaddr[i] + (((2 * ks + half) << 4) ^ aswz[i]));
+      for (int i = 0; i < NI; ++i) a[i] = *(const uint4*)(smem + (a0[i] ^ (ks << 5)));
 #pragma unroll
       for (int j = 0; j < NJ; ++j) b[j] = *(const uint4*)(wb + boff[j][ks]);
 #pragma unroll
@@ -714,7 +733,8 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     }                                                                                               \
     if (PS > 0 && (TAP) < 7) {                                                                      \
       const int cn = chunk + 1 < nchunks ? chunk + 1 : chunk;                                       \
-      _Pragma("unroll") for (int u = 0; u < PS; ++u) fill_patch((TAP) * PS + u, cn, (chunk + 1) & 1); \
+      _Pragma("unroll") for (int u = 0; u < PS; ++u)                                                \
+        dma16(psrc[((TAP) < 7 ? (TAP) : 0) * PS + u] + (size_t)cn * KB, patch_dst((TAP) * PS + u, (chunk + 1) & 1)); \
     }                                                                                               \
     compute(chunk, (TAP) / 3, (TAP) % 3, (TAP) % 3);                                                \
   }
@@ -828,6 +848,10 @@ bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
   if (PS == 0 ? nchunks != 1 : (nchunks < 2 || 7 * PS < fills_per_wave)) return false;
   const int smem = dg.tab_bytes + (PS > 0 ? 2 : 1) * dg.patch_rows * KB + 3 * BN * KB + 1024;
   if (smem > 160 * 1024 || p.zeros == nullptr) return false;
+  // pad rows come from the zero block; pad weight rows repeat row Nout-1 (columns past ldy are not stored);
+  // per-lane weight offsets are 32-bit
+  if (p.Cx * (int)sizeof(T) + 256 > kZeroBytes || p.ldy != p.Nout) return false;
+  if ((long long)p.Nout * 9 * p.Cx * (long long)sizeof(T) >= (1ll << 31)) return false;
   dg.smem_bytes = smem;
   static bool attr_set = false;
   if (!attr_set) {
@@ -841,15 +865,13 @@ bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
 }
 
 // Picks the tile for the asynchronous kernel; false if the problem is outside its range.
-// DDS_CONV_KB (64 or 128) is the channel-chunk depth in bytes: 64-byte rows halve the LDS
-// footprint so that two workgroups share a CU and hide each other's prologue and epilogue.
-#ifndef DDS_CONV_KB
-#define DDS_CONV_KB 64
-#endif
+// Channel chunks are 64 bytes deep: the LDS footprint lets two or three workgroups share a
+// CU and hide each other's prologue and epilogue, and with 16 rows per wave fill a patch of
+// up to 340 rows needs at most 6 fills per wave, so one slice per tap (PS = 1) is enough.
 template <typename T>
 bool launch_dma(const ConvParams& p, hipStream_t s) {
   HaloGeom h;
-  constexpr int KB = DDS_CONV_KB;
+  constexpr int KB = 64;
   const int rowbytes = p.Cx * (int)sizeof(T);
   if (rowbytes % KB != 0) return false;
   const int nchunks = rowbytes / KB;
@@ -861,18 +883,10 @@ bool launch_dma(const ConvParams& p, hipStream_t s) {
   // small images: 128-pixel tiles give more workgroups
   const long long tiles256 = (long long)((p.M + 255) / 256) * ((p.ldy + 127) / 128);
   if (tiles256 >= 512 && halo_geometry<T>(p, h, 256, KB)) {
-    if (p.ldy <= 64) {
-      if (launch_dma_inst<T, 256, 64, 64, 64, 1, KB>(p, h, s)) return true;
-      if (launch_dma_inst<T, 256, 64, 64, 64, 2, KB>(p, h, s)) return true;
-    }
+    if (p.ldy <= 64 && launch_dma_inst<T, 256, 64, 64, 64, 1, KB>(p, h, s)) return true;
     if (launch_dma_inst<T, 256, 128, 128, 64, 1, KB>(p, h, s)) return true;
-    if (launch_dma_inst<T, 256, 128, 128, 64, 2, KB>(p, h, s)) return true;
-    if (launch_dma_inst<T, 256, 128, 128, 64, 3, KB>(p, h, s)) return true;
   }
-  if (halo_geometry<T>(p, h, 128, KB)) {
-    if (launch_dma_inst<T, 128, 128, 64, 64, 1, KB>(p, h, s)) return true;
-    if (launch_dma_inst<T, 128, 128, 64, 64, 2, KB>(p, h, s)) return true;
-  }
+  if (halo_geometry<T>(p, h, 128, KB) && launch_dma_inst<T, 128, 128, 64, 64, 1, KB>(p, h, s)) return true;
   return false;
 }
 

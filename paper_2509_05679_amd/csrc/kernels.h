@@ -19,6 +19,10 @@ inline int dtype_ce(int dt) { return dt == DT_F32 ? 4 : 8; }
 //           ((h + pad - r)/stride, (w + pad - s)/stride) when divisible, w is the
 //           transposed weight snapshot [cin][tap][cout_padded]
 // epilogue: v = alpha * (acc + bias[n]); v += res[m, n]; relu; v = mask[m, n] > 0 ? v : 0
+// Size of the block of zeros every launch may read padding from: at least one pixel row
+// (all channels of one pixel) of any tensor the asynchronous kernels accept.
+constexpr int kZeroBytes = 16384;
+
 struct ConvParams {
   const void* x;
   const void* w;
@@ -26,7 +30,7 @@ struct ConvParams {
   const float* bias;  // fp32 [Nout] or null
   const void* res;    // same layout as y (dtype T) or null
   const void* mask;   // same layout as y (dtype T) or null
-  const void* zeros;  // at least 256 zero bytes (source of padding rows for LDS fills)
+  const void* zeros;  // kZeroBytes zero bytes (source of padding rows for LDS fills)
   int Nimg, H, W, Cx; // gathered tensor: NHWC, channel stride Cx (= GEMM-K per tap)
   int Ho, Wo;         // pixel grid of y; M = Nimg*Ho*Wo
   int M;
@@ -48,7 +52,7 @@ struct WgradParams {
   const void* dy;   // [P][ldy]
   const void* x;    // [Nimg][H][W][Cx]
   float* partial;   // [nsplit][Pl]
-  const void* zeros; // at least 256 zero bytes
+  const void* zeros; // kZeroBytes zero bytes
   int Nimg, H, W, Cx, Ho, Wo;
   int Mout;         // real output channels
   int ldy;
