@@ -232,97 +232,48 @@ __global__ __launch_bounds__(256) void softmax_ce_kernel(const float* logits, co
 }
 
 // ------------------------------------------------------------------ update
-// block_map[2*blk] = descriptor index, block_map[2*blk+1] = block within the descriptor
-// (1024 elements per block). Eight lanes share four consecutive elements: lane q sums the
-// splits q, q+8, q+16, ... in increasing order, then a fixed butterfly over the eight lanes
-// adds the partial sums, so the result is bit-reproducible whatever the split count while
-// eight split streams are read in parallel. g = sum/W; v = mu*v + g; w -= lr*v (or lr*g).
+// block_map[2*e] = descriptor index, block_map[2*e+1] = 1024-element block within the
+// descriptor; four workgroups share an entry, 256 consecutive elements each. Lane l of every
+// wave owns elements 4l..4l+3 of the workgroup's range; wave w sums the splits w, w+4, w+8, ...
+// (eight row reads in flight, each a fully coalesced 1 KiB), in a fixed order: eight interleaved
+// running sums, a fixed tree over them, then a fixed tree over the four waves through LDS. The
+// result is bit-reproducible for a given split count. g = sum/W; v = mu*v + g; w -= lr*v (or lr*g).
 template <typename T>
 __global__ __launch_bounds__(256) void update_kernel(const UpdateDesc* descs, const int* block_map, float invW, float lr, float mu) {
-  const UpdateDesc d = descs[block_map[2 * blockIdx.x]];
-  const long long blk0 = (long long)block_map[2 * blockIdx.x + 1] * 1024;
-  if (d.nsplit > 32) {
-    // many splits: one thread per four elements walks all splits (fully coalesced rows,
-    // eight loads in flight), fixed tree at the end
-    const long long base = blk0 + threadIdx.x * 4;
-    if (base >= d.n) return;
-    const bool vec = base + 4 <= d.n;
-    float4 s8[8];
+  const UpdateDesc d = descs[block_map[2 * (blockIdx.x >> 2)]];
+  const long long blk0 = (long long)block_map[2 * (blockIdx.x >> 2) + 1] * 1024 + (blockIdx.x & 3) * 256;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long long base = blk0 + lane * 4;
+  __shared__ float4 red[3][64];
+  float4 a[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s8[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < d.nsplit; j += 8) {
+  for (int u = 0; u < 8; ++u) a[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (base < d.n) {  // rows are pstride = n rounded up to 4 floats long: the vector read stays inside the row
+    const float* src = d.partial + base;
+    for (int j = wave; j < d.nsplit; j += 32) {
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        if (j + u < d.nsplit) {
-          const float* src = d.partial + (size_t)(j + u) * d.pstride + base;
-          if (vec) {
-            const float4 t = *(const float4*)src;
-            s8[u].x += t.x; s8[u].y += t.y; s8[u].z += t.z; s8[u].w += t.w;
-          } else {
-            s8[u].x += src[0];
-            if (base + 1 < d.n) s8[u].y += src[1];
-            if (base + 2 < d.n) s8[u].z += src[2];
-          }
+        const int jj = j + 4 * u;
+        if (jj < d.nsplit) {
+          const float4 t = *(const float4*)(src + (size_t)jj * d.pstride);
+          a[u].x += t.x; a[u].y += t.y; a[u].z += t.z; a[u].w += t.w;
         }
       }
     }
-#pragma unroll
-    for (int w = 4; w > 0; w >>= 1)
-#pragma unroll
-      for (int u = 0; u < w; ++u) { s8[u].x += s8[u + w].x; s8[u].y += s8[u + w].y; s8[u].z += s8[u + w].z; s8[u].w += s8[u + w].w; }
-    float g[4] = {s8[0].x * invW, s8[0].y * invW, s8[0].z * invW, s8[0].w * invW};
-    for (int e = 0; e < 4 && base + e < d.n; ++e) {
-      const long long i = base + e;
-      float w = d.master[i];
-      float gg = g[e];
-      if (d.momentum) { const float v = mu * d.momentum[i] + gg; d.momentum[i] = v; gg = v; }
-      w -= lr * gg;
-      d.master[i] = w;
-      if (d.work) {
-        if (sizeof(T) == 2) ((uint16_t*)d.work)[i] = f2bf(w);
-        else ((float*)d.work)[i] = w;
-      }
-    }
-    return;
-  }
-  const int q = threadIdx.x & 7;            // split lane
-  const int grp = threadIdx.x >> 3;         // 32 element groups of 4 per pass, 8 passes per block
-  float4 a[8];
-#pragma unroll
-  for (int pass = 0; pass < 8; ++pass) a[pass] = make_float4(0.f, 0.f, 0.f, 0.f);
-  // eight independent loads in flight per split; an element group past the end (or a ragged
-  // tail that cannot be read as one vector) is summed by the scalar path below
-  for (int j = q; j < d.nsplit; j += 8) {
-    const float* src = d.partial + (size_t)j * d.pstride + blk0 + grp * 4;
-#pragma unroll
-    for (int pass = 0; pass < 8; ++pass) {
-      const long long base = blk0 + (pass * 32 + grp) * 4;
-      if (base + 4 <= d.n) {
-        const float4 t = *(const float4*)(src + pass * 128);
-        a[pass].x += t.x; a[pass].y += t.y; a[pass].z += t.z; a[pass].w += t.w;
-      } else if (base < d.n) {
-        a[pass].x += src[pass * 128];
-        if (base + 1 < d.n) a[pass].y += src[pass * 128 + 1];
-        if (base + 2 < d.n) a[pass].z += src[pass * 128 + 2];
-      }
-    }
   }
 #pragma unroll
-  for (int pass = 0; pass < 8; ++pass) {
-    float4& s4 = a[pass];
+  for (int w = 4; w > 0; w >>= 1)
 #pragma unroll
-    for (int w = 4; w > 0; w >>= 1) {  // fixed butterfly: lanes q and q^w hold the same value afterwards
-      s4.x += __shfl_xor(s4.x, w, 8); s4.y += __shfl_xor(s4.y, w, 8); s4.z += __shfl_xor(s4.z, w, 8); s4.w += __shfl_xor(s4.w, w, 8);
-    }
+    for (int u = 0; u < w; ++u) { a[u].x += a[u + w].x; a[u].y += a[u + w].y; a[u].z += a[u + w].z; a[u].w += a[u + w].w; }
+  if (wave > 0) red[wave - 1][lane] = a[0];
+  __syncthreads();
+  if (wave > 0 || base >= d.n) return;
+  {
+    const float4 r1 = red[0][lane], r2 = red[1][lane], r3 = red[2][lane];
+    a[0].x = (a[0].x + r1.x) + (r2.x + r3.x); a[0].y = (a[0].y + r1.y) + (r2.y + r3.y);
+    a[0].z = (a[0].z + r1.z) + (r2.z + r3.z); a[0].w = (a[0].w + r1.w) + (r2.w + r3.w);
   }
-  // lane q finishes pass q of its group: all 256 threads write
-  float4 mine = a[0];
-#pragma unroll
-  for (int pass = 1; pass < 8; ++pass)
-    if (q == pass) mine = a[pass];
-  const long long base = blk0 + (q * 32 + grp) * 4;
-  if (base >= d.n) return;
-  float g[4] = {mine.x * invW, mine.y * invW, mine.z * invW, mine.w * invW};
+  float g[4] = {a[0].x * invW, a[0].y * invW, a[0].z * invW, a[0].w * invW};
   if (base + 4 <= d.n) {
     float4 w = *(const float4*)(d.master + base);
     if (d.momentum) {
@@ -463,7 +414,7 @@ void launch_softmax_ce(int dt, const float* logits, const int32_t* labels, void*
 void launch_update(int dt, const UpdateDesc* descs, const int* block_map, int total_blocks, int W, float lr, float mu,
                    hipStream_t s) {
   if (total_blocks <= 0) return;
-  DDS_DISPATCH(dt, update_kernel, <<<total_blocks, 256, 0, s>>>(descs, block_map, 1.f / (float)W, lr, mu));
+  DDS_DISPATCH(dt, update_kernel, <<<4 * total_blocks, 256, 0, s>>>(descs, block_map, 1.f / (float)W, lr, mu));
 }
 
 void launch_recast(int dt, const UpdateDesc* descs, const int* block_map, int total_blocks, hipStream_t s) {
