@@ -12,6 +12,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -151,6 +152,8 @@ struct dds_ctx {
   int64_t launches = 0;
   double gemm_flops = 0.0;
   size_t arena_used = 0;
+  bool serial = false;  // DDS_SERIAL=1 in the environment at dds_create: modules run one after another on the
+                        // caller's stream (per-kernel timing without other modules sharing the chip)
   // optional per-launch timing of the MFMA kernels (events on the launching stream)
   bool profiling = false;
   struct ProfRec { int cls; double flops; hipEvent_t a, b; };
@@ -820,6 +823,10 @@ int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* aren
   if (e != hipSuccess) { delete c; return fail(DDS_EHIP, "hipMemset(arena) failed: %s", hipGetErrorString(e)); }
   rc = upload_tables(*c);
   if (rc) { delete c; return rc; }
+  {
+    const char* env = getenv("DDS_SERIAL");
+    c->serial = env && env[0] == '1';
+  }
   e = hipEventCreateWithFlags(&c->fork, hipEventDisableTiming);
   if (e != hipSuccess) { delete c; return fail(DDS_EHIP, "hipEventCreate failed: %s", hipGetErrorString(e)); }
   if (K > 1) {
@@ -904,7 +911,7 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
     launch_ingest(c->dt, p, us);
     ++c->launches;
   }
-  const bool multi = c->K > 1;
+  const bool multi = c->K > 1 && !c->serial;
   if (multi) HIP_TRY(hipEventRecord(c->fork, us));
   for (int k0 = 0; k0 < c->K; ++k0) {
     Module& m = c->mods[k0];

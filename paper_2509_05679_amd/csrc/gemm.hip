@@ -233,8 +233,13 @@ __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_
 }
 
 // ------------------------------------------------------------------ forward / dgrad
-template <typename T, int BM, int BN, int WM, int WN, int BKB, bool DGRAD>
-__global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p) {
+// S2 (dgrad of a stride-2 convolution whose channel count is a multiple of the k-tile): the
+// output pixels are dealt to workgroups by parity class (h % 2, w % 2), blockIdx.x =
+// class * tiles_per_class + tile. A pixel of class (ch, cw) only receives taps r = ch + pad,
+// s = cw + pad (mod 2), so a workgroup walks just those taps: on average 2.25 of the 9 taps
+// of a 3x3 kernel, and 1 class in 4 has any tap at all for a 1x1 kernel.
+template <typename T, int BM, int BN, int WM, int WN, int BKB, bool DGRAD, bool S2 = false>
+__global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int tiles_per_class) {
   constexpr int ES = sizeof(T);
   constexpr int CE = 16 / ES;     // elements per 16-byte chunk
   constexpr int BKE = BKB / ES;   // k elements per tile
@@ -248,22 +253,41 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave % (BM / WM), wave_n = wave / (BM / WM);
-  const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+  const int cls = S2 ? blockIdx.x / tiles_per_class : 0;
+  const int ch = cls >> 1, cw = cls & 1;
+  const int Hc = (p.Ho - ch + 1) >> 1, Wc = (p.Wo - cw + 1) >> 1;  // pixels of this class per image column / row
+  const int Mc = S2 ? p.Nimg * Hc * Wc : p.M;
+  const int m0 = (S2 ? blockIdx.x - cls * tiles_per_class : blockIdx.x) * BM, n0 = blockIdx.y * BN;
   const int chunk = tid % CPR, rbase = tid / CPR;
   const int sh = p.stride - 1;  // stride is 1 or 2
+  // row of the tile -> output pixel (image, oh, ow) and its flat index
+  auto row_pixel = [&](int m, int& img, int& oh, int& ow) {
+    if (S2) {
+      const int HW = Hc * Wc;
+      img = m / HW;
+      const int rem = m - img * HW;
+      const int h2 = rem / Wc;
+      oh = 2 * h2 + ch;
+      ow = 2 * (rem - h2 * Wc) + cw;
+    } else {
+      const int HoWo = p.Ho * p.Wo;
+      img = m / HoWo;
+      const int rem = m - img * HoWo;
+      oh = rem / p.Wo;
+      ow = rem - oh * p.Wo;
+    }
+  };
 
   int a_h[AP], a_w[AP];
   const char* a_base[AP];
   bool a_ok[AP];
-  const int HoWo = p.Ho * p.Wo;
 #pragma unroll
   for (int i = 0; i < AP; ++i) {
     int m = m0 + rbase + i * ROWS;
-    a_ok[i] = m < p.M;
+    a_ok[i] = m < Mc;
     int mm = a_ok[i] ? m : 0;
-    int img = mm / HoWo;
-    int rem = mm - img * HoWo;
-    int oh = rem / p.Wo, ow = rem - oh * p.Wo;
+    int img, oh, ow;
+    row_pixel(mm, img, oh, ow);
     if (DGRAD) { a_h[i] = oh + p.pad; a_w[i] = ow + p.pad; }
     else { a_h[i] = oh * p.stride - p.pad; a_w[i] = ow * p.stride - p.pad; }
     a_base[i] = (const char*)p.x + (size_t)img * p.H * p.W * p.Cx * ES;
@@ -330,13 +354,37 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
 
-  const int nk = (p.Ktot + BKE - 1) / BKE;
-  load_global();
-  store_lds(0);
+  // S2: taps of the wrong parity are stepped over whole (Cx / BKE k-tiles at a time; the
+  // position is the same for every thread of the workgroup up to the chunk offset)
+  const int tiles_per_tap = S2 ? p.Cx / BKE : 1;
+  auto tap_live = [&]() { return ((ch + p.pad - kr) & 1) == 0 && ((cw + p.pad - ks) & 1) == 0; };
+  auto skip_dead_taps = [&]() {
+    if (S2) {
+      while (kr < p.R && !tap_live()) {
+        kflat += p.Cx;
+        if (++ks == p.S) { ks = 0; ++kr; }
+      }
+    }
+  };
+  int nk = (p.Ktot + BKE - 1) / BKE;
+  if (S2) {
+    int nr = 0, ns = 0;
+    for (int r = 0; r < p.R; ++r) nr += ((ch + p.pad - r) & 1) == 0;
+    for (int q = 0; q < p.S; ++q) ns += ((cw + p.pad - q) & 1) == 0;
+    nk = nr * ns * tiles_per_tap;
+  }
+  if (nk > 0) {
+    skip_dead_taps();
+    load_global();
+    store_lds(0);
+  }
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) load_global();
+    if (kt + 1 < nk) {
+      skip_dead_taps();
+      load_global();
+    }
     const char* As = smem + buf * (BM + BN) * LDK + wave_m * WM * LDK;
     const char* Bs = smem + buf * (BM + BN) * LDK + BM * LDK + wave_n * WN * LDK;
     // weights are the MFMA A operand so that a lane ends up with 4 consecutive output
@@ -353,7 +401,13 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p) {
 #pragma unroll
   for (int i = 0; i < WM / 32; ++i) {
     const int m = m0 + wave_m * WM + i * 32 + (lane & 31);
-    epilogue_tile<T, WN / 32, WM / 32>(p, acc, i, m < p.M, (size_t)m, nb, bias);
+    size_t pix = (size_t)m;
+    if (S2) {
+      int img, oh, ow;
+      row_pixel(m < Mc ? m : 0, img, oh, ow);
+      pix = ((size_t)img * p.Ho + oh) * p.Wo + ow;
+    }
+    epilogue_tile<T, WN / 32, WM / 32>(p, acc, i, m < Mc, pix, nb, bias);
   }
 }
 
@@ -1255,14 +1309,21 @@ void launch_conv_t(const ConvParams& p, hipStream_t s) {
     else launch_halo_inst<T, 128, 128, 64, HALO_BKB>(p, g, s);
     return;
   }
+  // dgrad of a stride-2 convolution: workgroups per parity class (class (0,0) is the largest)
+  const bool s2 = p.dgrad && p.stride == 2 && p.Cx % (BKB / (int)sizeof(T)) == 0;
+  const int mc = p.Nimg * ((p.Ho + 1) / 2) * ((p.Wo + 1) / 2);
   if (p.ldy <= 64) {
-    dim3 grid(cdiv(p.M, 256), cdiv(p.ldy, 64));
-    if (p.dgrad) conv_gemm_kernel<T, 256, 64, 64, 64, BKB, true><<<grid, 256, 0, s>>>(p);
-    else conv_gemm_kernel<T, 256, 64, 64, 64, BKB, false><<<grid, 256, 0, s>>>(p);
+    const int tpc = cdiv(mc, 256);
+    dim3 grid(s2 ? 4 * tpc : cdiv(p.M, 256), cdiv(p.ldy, 64));
+    if (s2) conv_gemm_kernel<T, 256, 64, 64, 64, BKB, true, true><<<grid, 256, 0, s>>>(p, tpc);
+    else if (p.dgrad) conv_gemm_kernel<T, 256, 64, 64, 64, BKB, true><<<grid, 256, 0, s>>>(p, 0);
+    else conv_gemm_kernel<T, 256, 64, 64, 64, BKB, false><<<grid, 256, 0, s>>>(p, 0);
   } else {
-    dim3 grid(cdiv(p.M, 128), cdiv(p.ldy, 128));
-    if (p.dgrad) conv_gemm_kernel<T, 128, 128, 64, 64, BKB, true><<<grid, 256, 0, s>>>(p);
-    else conv_gemm_kernel<T, 128, 128, 64, 64, BKB, false><<<grid, 256, 0, s>>>(p);
+    const int tpc = cdiv(mc, 128);
+    dim3 grid(s2 ? 4 * tpc : cdiv(p.M, 128), cdiv(p.ldy, 128));
+    if (s2) conv_gemm_kernel<T, 128, 128, 64, 64, BKB, true, true><<<grid, 256, 0, s>>>(p, tpc);
+    else if (p.dgrad) conv_gemm_kernel<T, 128, 128, 64, 64, BKB, true><<<grid, 256, 0, s>>>(p, 0);
+    else conv_gemm_kernel<T, 128, 128, 64, 64, BKB, false><<<grid, 256, 0, s>>>(p, 0);
   }
 }
 
