@@ -436,7 +436,17 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
       ParamLayer& L = m.layers[nd.layer];
       const Tensor& to = m.tensors[nd.out];
       const int P = c.N * to.H * to.W;
-      L.nsplit = wgrad_choose_split(c.dt, L.Cout, L.RS * L.Cinpad, P, c.W);
+      {
+        const Tensor& tin = m.tensors[nd.in];
+        WgradParams w{};
+        w.zeros = &w;  // non-null: only the shape matters here
+        w.Nimg = c.N; w.H = tin.H; w.W = tin.W; w.Cx = tin.Cpad; w.Ho = to.H; w.Wo = to.W;
+        w.Mout = L.Cout; w.ldy = to.Cpad;
+        w.R = L.R; w.S = L.R; w.stride = L.stride; w.pad = L.pad;
+        w.NK = L.RS * L.Cinpad;
+        w.P = P;
+        L.nsplit = wgrad_choose_split(c.dt, w, c.W);
+      }
       L.partial = (float*)A.take((size_t)L.nsplit * L.pstride * 4);
       if (L.need_stash) {
         L.stash_elems = (long long)L.Cin * L.RS * L.Coutpad;

@@ -1152,38 +1152,61 @@ __device__ __forceinline__ uint2 lds_tr16(const char* p) {
   return __builtin_bit_cast(uint2, v);
 }
 
-template <int TWLOG, int PF>
-__global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, HaloGeom g, const void* zeros) {
-  constexpr int TW = 1 << TWLOG, PW = TW + 2;
+// Geometry the host passes along with WgradParams.
+struct WgradGeom {
+  int tiles_h;     // 128-pixel tiles per image (a power of two; 1 when a tile holds whole images)
+  int cblocks;     // 64-channel blocks of the real input tensor
+  int sub[4];      // S2: sub-pixel (dy * 2 + dx) served by blockIdx.y / cblocks
+  int rmap[2][2];  // S2: real kernel row for (virtual row R', dy), -1 if none; the same table serves columns
+};
+
+// S2 = false: 3x3, stride 1, pad 1 (nine taps, TW x TH tiles of the image itself).
+// S2 = true: a stride-2 convolution (3x3 pad 1, or 1x1 pad 0) seen as a stride-1 one on the
+// input regrouped into 2x2 sub-pixels: output pixel (oy, ox) and real tap r read input row
+// 2*oy + r - pad, i.e. sub-pixel row dy of super-pixel row oy - 1 or oy. A workgroup takes the
+// 64 channels of ONE sub-pixel (dy, dx); its patch is that sub-grid (gathered at pixel stride
+// 2 by the fills) and only the virtual taps R', S' in {0, 1} that a real tap maps to are
+// accumulated: 1, 2, 2 and 4 of them for the four sub-pixels of a 3x3 kernel, none wasted.
+__device__ __forceinline__ uint2 lds_tr16_at(uint32_t lds_byte_address) {
+  s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4_t DDS_LDS_AS*)(size_t)lds_byte_address);
+  return __builtin_bit_cast(uint2, v);
+}
+
+template <int TWLOG, int THLOG, bool S2>
+__global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradGeom wg, const void* zeros) {
+  constexpr int TW = 1 << TWLOG, TH = 1 << THLOG, PW = TW + 2, PP = (TH + 2) * PW;
+  constexpr int IMGS = 128 / (TW * TH);
+  static_assert(IMGS >= 1 && IMGS * TW * TH == 128, "a tile is 128 pixels");
+  constexpr int PROW = (IMGS * PP + 7) / 8 * 8;   // patch rows, whole 8-row fills
+  constexpr int PF = (PROW / 8 + 3) / 4;          // patch fills per wave
   constexpr int NF = 4 + PF;  // fills per lane per tile: 4 (dY) + PF (patch; surplus ones go to a dump block)
-  constexpr int TAB = PF > 7 ? 2048 : 1024;
+  constexpr int NT = S2 ? 4 : 9;                  // accumulated taps
+  constexpr int SLOT = 16384 + PROW * 128;
   extern __shared__ __align__(16) char smem[];
-  const int prow = (g.patch_pix + 7) / 8 * 8;
-  const int slot_bytes = 16384 + prow * 128;
-  char* ring = smem + TAB;
-  const uint32_t lds_ring = (uint32_t)(size_t)(DDS_LDS_AS char*)smem + TAB;
-  const uint32_t lds_dump = lds_ring + 3 * slot_bytes;
+  const uint32_t lds_ring = (uint32_t)(size_t)(DDS_LDS_AS char*)smem;
+  const uint32_t lds_dump = lds_ring + 3 * SLOT;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wave_m = wave & 1, wave_n = wave >> 1;
-  const int k0 = blockIdx.x * 64, c0 = blockIdx.y * 64, z = blockIdx.z;
-  const int tiles_per_img = g.tiles_h;         // TW == image width
-  const int THm = (1 << g.th_log) - 1;
+  const int k0 = blockIdx.x * 64, z = blockIdx.z;
+  const int sub = S2 ? wg.sub[blockIdx.y / wg.cblocks] : 0;
+  const int sdy = sub >> 1, sdx = sub & 1;
+  const int c0 = (S2 ? blockIdx.y % wg.cblocks : blockIdx.y) * 64;
   const int tile0 = z * (p.pix_per_split >> 7);
   const int ntiles = p.pix_per_split >> 7;
   const size_t ybytes = (size_t)p.ldy * 2, xbytes = (size_t)p.Cx * 2;
 
-  // A tile is 128 consecutive pixels of the flattened (image, row, column) index, so the
-  // source address of every fill advances by a constant from tile to tile; what is kept
-  // per lane and fill is the byte offset of its patch row relative to the tile origin and
+  // A tile is 128 consecutive pixels of the flattened (image, row, column) index of the output
+  // grid, so the source address of every fill advances by a constant from tile to tile; what is
+  // kept per lane and fill is the byte offset of its patch row relative to the tile origin and
   // the row / column facts that decide whether that row is padding.
   const int l8 = lane >> 3;
   const int c16 = ((lane & 7) ^ ((l8 & 3) << 1)) * 16;  // global 16-byte column for LDS slot lane&7 of a row with row&3 == l8&3
   const char* zsrc = (const char*)zeros + c16;
-  const int pw_total = prow >> 3;
+  constexpr int pw_total = PROW >> 3;
   const bool ycol_ok = k0 + (c16 >> 1) < p.ldy;   // this lane's 8 output channels exist
-  const size_t tile_ybytes = 128 * ybytes, tile_xbytes = 128 * xbytes;
+  const size_t tile_ybytes = 128 * ybytes, tile_xbytes = (S2 ? 4 : 1) * 128 * xbytes;
   const char* ysrc0 = (const char*)p.dy + ((size_t)tile0 * 128 + (size_t)(wave * 8 + l8)) * ybytes + (size_t)k0 * 2 + c16;
   const char* xsrc0 = (const char*)p.x + (size_t)tile0 * tile_xbytes + (size_t)c0 * 2 + c16;
   int prel[PF], pflag[PF];  // byte offset from the tile origin; yy | column valid << 8
@@ -1191,21 +1214,22 @@ __global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, Hal
   for (int u = 0; u < PF; ++u) {
     const int row = (wave + 4 * u) * 8 + l8;
     int rel = 0, flag = 0;
-    if (row < g.patch_pix) {
-      const int im = row / g.PP, rem = row - im * g.PP;
+    if (row < IMGS * PP) {
+      const int im = row / PP, rem = row - im * PP;
       const int yy = rem / PW, xx = rem - yy * PW;
-      rel = (int)((((long long)im * p.H + yy - 1) * p.W + (xx - 1)) * (long long)xbytes);
-      flag = yy | (((unsigned)(xx - 1) < (unsigned)p.W ? 1 : 0) << 8);
+      if (S2) rel = (int)((((long long)im * p.H + 2 * (yy - 1) + sdy) * p.W + 2 * (xx - 1) + sdx) * (long long)xbytes);
+      else rel = (int)((((long long)im * p.H + yy - 1) * p.W + (xx - 1)) * (long long)xbytes);
+      flag = yy | (((unsigned)(xx - 1) < (unsigned)p.Wo ? 1 : 0) << 8);
     }
     prel[u] = rel;
     pflag[u] = flag;
   }
-  const int tile_in_img_mask = tiles_per_img - 1;  // tiles per image is a power of two
+  const int tile_in_img_mask = wg.tiles_h - 1;
   auto fill_tile = [&](int t, int slot) {  // t: tile index inside this split (fills nothing real past the end)
     const bool live_t = t < ntiles;
     const int tt = live_t ? t : 0;
-    const int h0 = ((tile0 + tt) & tile_in_img_mask) << g.th_log;
-    const uint32_t base = lds_ring + slot * slot_bytes;
+    const int h0 = ((tile0 + tt) & tile_in_img_mask) << THLOG;
+    const uint32_t base = lds_ring + slot * SLOT;
     const char* ysrc = ysrc0 + (size_t)tt * tile_ybytes;
     const char* xsrc = xsrc0 + (size_t)tt * tile_xbytes;
     const bool yok = live_t && ycol_ok;
@@ -1217,7 +1241,7 @@ __global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, Hal
       const int wl = wave + 4 * u;
       const bool live = live_t && wl < pw_total;
       const int gh = h0 + (pflag[u] & 255) - 1;
-      const bool ok = live && (pflag[u] >> 8) && (unsigned)gh < (unsigned)p.H;
+      const bool ok = live && (pflag[u] >> 8) && (unsigned)gh < (unsigned)p.Ho;
       dma16(ok ? xsrc + prel[u] : zsrc, live ? base + 16384 + wl * 1024 : lds_dump);
     }
   };
@@ -1228,12 +1252,36 @@ __global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, Hal
   // A (dY): rows are tile pixels; row & 3 == rsub for every block this lane reads
   const int a_c = 4 * wave_m + 2 * grp16 + (seg >> 1);
   const int a_lane = (8 * khalf + rsub) * 128 + ((a_c ^ (rsub << 1)) << 4) + 8 * (seg & 1);
+  // B (patch): k-step ks covers tile pixels 16 ks + ql, ql = 8 khalf + rsub + 4 hh for this
+  // lane's two 4-pixel blocks hh. The patch row of such a pixel splits into a per-lane part
+  // (kept in registers, one copy per value v of (row + tap offset) & 3 that the column
+  // swizzle depends on) and a part that only depends on (ks, tap): a compile-time offset.
   const int b_c = 4 * wave_n + 2 * grp16 + (seg >> 1);
-  const int b_off8 = 8 * (seg & 1);
-
-  f32x16_t acc[9], accb;
+  int baddr[2][4];
 #pragma unroll
-  for (int t = 0; t < 9; ++t)
+  for (int hh = 0; hh < 2; ++hh) {
+    const int ql = 8 * khalf + rsub + 4 * hh;
+    const int rl = (ql >> TWLOG) * PW + (ql & (TW - 1));
+#pragma unroll
+    for (int v = 0; v < 4; ++v) baddr[hh][v] = rl * 128 + ((b_c ^ (((rl + v) & 3) << 1)) << 4) + 8 * (seg & 1);
+  }
+  bool live[NT];
+  int tapreal[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    if (S2) {
+      const int rr = wg.rmap[t >> 1][sdy], ss = wg.rmap[t & 1][sdx];
+      live[t] = rr >= 0 && ss >= 0;
+      tapreal[t] = rr * p.S + ss;
+    } else {
+      live[t] = true;
+      tapreal[t] = t;
+    }
+  }
+
+  f32x16_t acc[NT], accb;
+#pragma unroll
+  for (int t = 0; t < NT; ++t)
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
 #pragma unroll
@@ -1246,36 +1294,39 @@ __global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, Hal
     wait_vm<NF>();  // everything but the youngest tile's fills has landed
     wg_barrier();
     fill_tile(t + 2, (t + 2) % 3);
-    const char* ybuf = ring + (t % 3) * slot_bytes;
-    const char* xbuf = ybuf + 16384;
+    uint32_t ybuf = lds_ring + (t % 3) * SLOT + a_lane;
+    uint32_t bp[2][4];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        bp[hh][v] = lds_ring + (t % 3) * SLOT + 16384 + baddr[hh][v];
+        // opaque: otherwise every (lane part + compile-time part) sum is precomputed outside the
+        // tile loop, one register each, instead of riding in the instruction's offset field
+        asm volatile("" : "+v"(bp[hh][v]));
+      }
+    asm volatile("" : "+v"(ybuf));
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {  // 16 pixels per step
-      // patch rows of this lane's pixels q and q+4
-      int vb[2][4];  // [which half][row & 3 shift] -> byte address of the (tap-less) block row
-#pragma unroll
-      for (int hh = 0; hh < 2; ++hh) {
-        int q = ks * 16 + 8 * khalf + rsub + 4 * hh;
-        asm volatile("" : "+v"(q));
-        const int x = q & (TW - 1), y = (q >> TWLOG) & THm, im = q >> (TWLOG + g.th_log);
-        const int R = im * g.PP + y * PW + x;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) vb[hh][d] = R * 128 + ((b_c ^ (((R + d) & 3) << 1)) << 4) + b_off8;
-      }
-      uint2 a0 = lds_tr16(ybuf + a_lane + ks * 2048);
-      uint2 a1 = lds_tr16(ybuf + a_lane + ks * 2048 + 512);
+      constexpr int dummy = 0; (void)dummy;
+      const int q0 = ks * 16;
+      const int rc = (q0 >> (TWLOG + THLOG)) * PP + ((q0 >> TWLOG) & (TH - 1)) * PW + (q0 & (TW - 1));  // compile-time after unrolling
+      uint2 a0 = lds_tr16_at(ybuf + ks * 2048);
+      uint2 a1 = lds_tr16_at(ybuf + ks * 2048 + 512);
       const uint4 af = make_uint4(a0.x, a0.y, a1.x, a1.y);
 #pragma unroll
-      for (int tap = 0; tap < 9; ++tap) {
-        constexpr int dummy = 0; (void)dummy;
-        const int tr = tap / 3, ts = tap % 3;
-        const int toff = tr * PW + ts;       // compile-time; PW & 3 == 2 for every supported width
-        const int d = toff & 3;
-        uint2 b0 = lds_tr16(xbuf + vb[0][d] + toff * 128);
-        uint2 b1 = lds_tr16(xbuf + vb[1][d] + toff * 128);
-        const uint4 bf = make_uint4(b0.x, b0.y, b1.x, b1.y);
-        mfma16B<bf16_t>(af, bf, acc[tap]);
+      for (int tap = 0; tap < NT; ++tap) {
+        const int toff = S2 ? (tap >> 1) * PW + (tap & 1) : (tap / 3) * PW + tap % 3;
+        const int v = (rc + toff) & 3;
+        if (!S2 || live[tap]) {
+          uint2 b0 = lds_tr16_at(bp[0][v] + (rc + toff) * 128);
+          uint2 b1 = lds_tr16_at(bp[1][v] + (rc + toff) * 128);
+          const uint4 bf = make_uint4(b0.x, b0.y, b1.x, b1.y);
+          mfma16B<bf16_t>(af, bf, acc[tap]);
+        }
       }
-      if (wave_n == 0) mfma16B<bf16_t>(af, ones, accb);
+      if (wave_n == 0 && blockIdx.y == 0) mfma16B<bf16_t>(af, ones, accb);  // bias gradient: column sums of dY
+      __builtin_amdgcn_sched_barrier(0);  // keep the reads of later k-steps from being hoisted (register pressure)
     }
   }
   wait_vm<0>();
@@ -1288,7 +1339,8 @@ __global__ __launch_bounds__(256, 2) void wgrad3x3_dma_kernel(WgradParams p, Hal
     if (k >= p.Mout) continue;
     if (cin < p.Cx) {
 #pragma unroll
-      for (int tap = 0; tap < 9; ++tap) out[(size_t)k * p.NK + tap * p.Cx + cin] = p.alpha * acc[tap][e];
+      for (int tap = 0; tap < NT; ++tap)
+        if (live[tap]) out[(size_t)k * p.NK + tapreal[tap] * p.Cx + cin] = p.alpha * acc[tap][e];
     }
     if (wave_n == 0 && (lane & 31) == 0 && blockIdx.y == 0) out[(size_t)p.Mout * p.NK + k] = p.alpha * accb[e];
   }
@@ -1327,39 +1379,74 @@ void launch_conv_t(const ConvParams& p, hipStream_t s) {
   }
 }
 
-template <int TWLOG, int PF>
-void launch_wgrad_dma_inst(const WgradParams& p, const HaloGeom& g, hipStream_t s) {
+template <int TWLOG, int THLOG, bool S2>
+void launch_wgrad_dma_inst(const WgradParams& p, const WgradGeom& wg, int nsub, hipStream_t s) {
+  constexpr int TW = 1 << TWLOG, TH = 1 << THLOG;
+  constexpr int PROW = ((128 / (TW * TH)) * (TH + 2) * (TW + 2) + 7) / 8 * 8;
   static bool attr_set = false;
   if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)wgrad3x3_dma_kernel<TWLOG, PF>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    (void)hipFuncSetAttribute((const void*)wgrad_dma_kernel<TWLOG, THLOG, S2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_set = true;
   }
-  const int prow = (g.patch_pix + 7) / 8 * 8;
-  const int smem = (PF > 7 ? 2048 : 1024) + 3 * (16384 + prow * 128) + 1024;
-  dim3 grid(cdiv(p.Mout, 64), p.Cx / 64, p.nsplit);
-  wgrad3x3_dma_kernel<TWLOG, PF><<<grid, 256, smem, s>>>(p, g, p.zeros);
+  const int smem = 3 * (16384 + PROW * 128) + 1024;
+  dim3 grid(cdiv(p.Mout, 64), nsub * wg.cblocks, p.nsplit);
+  wgrad_dma_kernel<TWLOG, THLOG, S2><<<grid, 256, smem, s>>>(p, wg, p.zeros);
 }
 
-// bf16 3x3 stride-1 problems whose splits are whole 128-pixel tiles go to the asynchronous kernel
-bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
-  if (p.R != 3 || p.S != 3 || p.stride != 1 || p.pad != 1 || p.H != p.Ho || p.W != p.Wo) return false;
+// bf16 problems whose splits are whole 128-pixel tiles go to the asynchronous kernel: 3x3
+// stride 1 pad 1, and the stride-2 layers (3x3 pad 1, 1x1 pad 0) on even-sized images.
+// On success: sub-pixels served (1 for stride 1), 64-channel blocks, tile geometry.
+bool wgrad_dma_eligible(const WgradParams& p, int* nsub_out, int* cblocks_out, int* lw_out = nullptr, int* th_log_out = nullptr,
+                        int* tiles_h_out = nullptr) {
+  const bool s1 = p.R == 3 && p.S == 3 && p.stride == 1 && p.pad == 1 && p.H == p.Ho && p.W == p.Wo;
+  const bool s2 = p.stride == 2 && p.R == p.S && ((p.R == 3 && p.pad == 1) || (p.R == 1 && p.pad == 0)) &&
+                  p.H == 2 * p.Ho && p.W == 2 * p.Wo;
+  if (!s1 && !s2) return false;
   if (p.Cx % 64 != 0 || p.zeros == nullptr || p.pix_per_split % 128 != 0 || p.P % 128 != 0) return false;
-  ConvParams c{};
-  c.R = c.S = 3; c.stride = 1; c.pad = 1; c.H = c.Ho = p.H; c.W = c.Wo = p.W; c.Cx = p.Cx; c.out_f32 = 0; c.dgrad = 0;
-  HaloGeom g;
-  if (!halo_geometry<bf16_t>(c, g, 128, 128)) return false;
-  const int prow = (g.patch_pix + 7) / 8 * 8;
-  const int fills = (prow / 8 + 3) / 4;  // patch fills per wave
-  if (fills <= 7) {
-    switch (g.tw_log) {
-      case 2: launch_wgrad_dma_inst<2, 7>(p, g, s); return true;
-      case 3: launch_wgrad_dma_inst<3, 7>(p, g, s); return true;
-      case 4: launch_wgrad_dma_inst<4, 7>(p, g, s); return true;
-      case 5: launch_wgrad_dma_inst<5, 7>(p, g, s); return true;
-      default: return false;
+  // byte offsets of patch rows relative to the tile origin are 32-bit
+  if ((long long)(128 + 2 * p.W + 4) * 4 * p.Cx * 2 >= (1ll << 31) || p.Cx * 2 + 256 > kZeroBytes) return false;
+  const int lw = ilog2_exact(p.Wo), lh = ilog2_exact(p.Ho);
+  if (lw < 2 || lh < 0 || p.Wo > 32) return false;
+  int th_log, tiles_h;
+  if (p.Ho * p.Wo >= 128) { th_log = 7 - lw; tiles_h = p.Ho >> th_log; if (th_log > lh) return false; }
+  else { th_log = lh; tiles_h = 1; }
+  if (!((lw == 5 && th_log == 2) || (lw == 4 && th_log == 3) || (lw == 3 && th_log == 3) || (lw == 2 && th_log == 2))) return false;
+  *nsub_out = s2 && p.R == 3 ? 4 : 1;
+  *cblocks_out = p.Cx / 64;
+  if (lw_out) *lw_out = lw;
+  if (th_log_out) *th_log_out = th_log;
+  if (tiles_h_out) *tiles_h_out = tiles_h;
+  return true;
+}
+
+bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
+  int nsub_e, cblocks, lw, th_log, tiles_h;
+  if (!wgrad_dma_eligible(p, &nsub_e, &cblocks, &lw, &th_log, &tiles_h)) return false;
+  const bool s2 = p.stride == 2;
+  WgradGeom wg{};
+  wg.tiles_h = tiles_h;
+  wg.cblocks = p.Cx / 64;
+  int nsub = 1;
+  if (s2) {
+    // real tap for (virtual tap, sub-pixel offset): 3x3 pad 1: rows 2oy-1, 2oy, 2oy+1; 1x1 pad 0: row 2oy
+    if (p.R == 3) { wg.rmap[0][0] = -1; wg.rmap[0][1] = 0; wg.rmap[1][0] = 1; wg.rmap[1][1] = 2; }
+    else { wg.rmap[0][0] = -1; wg.rmap[0][1] = -1; wg.rmap[1][0] = 0; wg.rmap[1][1] = -1; }
+    nsub = 0;
+    // heaviest sub-pixels first: (1,1) accumulates four taps, (0,0) one
+    for (int sub = 3; sub >= 0; --sub) {
+      const int dy = sub >> 1, dx = sub & 1;
+      const bool any_r = wg.rmap[0][dy] >= 0 || wg.rmap[1][dy] >= 0, any_s = wg.rmap[0][dx] >= 0 || wg.rmap[1][dx] >= 0;
+      if (any_r && any_s) wg.sub[nsub++] = sub;
     }
   }
-  if (fills <= 9 && prow * 4 <= 2048 && g.tw_log == 2) { launch_wgrad_dma_inst<2, 9>(p, g, s); return true; }
+#define DDS_WG_CASE(TWL, THL)                                                        \
+  if (lw == TWL && th_log == THL) {                                                  \
+    if (s2) launch_wgrad_dma_inst<TWL, THL, true>(p, wg, nsub, s);                   \
+    else launch_wgrad_dma_inst<TWL, THL, false>(p, wg, nsub, s);                     \
+    return true;                                                                     \
+  }
+  DDS_WG_CASE(5, 2) DDS_WG_CASE(4, 3) DDS_WG_CASE(3, 3) DDS_WG_CASE(2, 2)
+#undef DDS_WG_CASE
   return false;
 }
 
@@ -1388,16 +1475,37 @@ void launch_wgrad(int dt, const WgradParams& p, hipStream_t s) {
   else launch_wgrad_t<bf16_t>(p, s);
 }
 
-int wgrad_choose_split(int dt, int Mout, int NK, int P, int W) {
+int wgrad_choose_split(int dt, const WgradParams& shape, int W) {
+  const int Mout = shape.Mout, NK = shape.NK, P = shape.P;
+  const int per_replica = P / W;  // pixels of one replica's mini-batch
+  if (dt != DT_F32) {
+    // Asynchronous kernel: 64 x 64 output blocks per (sub-pixel, channel block); splits are whole
+    // 128-pixel tiles. Take the fewest splits that give every CU a workgroup: the partial sums
+    // cost HBM traffic (written here, read by the update) in proportion to the split count, and
+    // measured on the ResNet-18 step 256 workgroups beat 512 and 1024 (2.95 / 3.13 / 3.45 ms).
+    WgradParams probe = shape;
+    probe.nsplit = W;
+    probe.pix_per_split = 128;
+    int nsub = 0, cblocks = 0;
+    if (wgrad_dma_eligible(probe, &nsub, &cblocks)) {
+      const int blocks = cdiv(Mout, 64) * nsub * cblocks;
+      int best = 0;
+      for (int q = 1; q * W <= 256; ++q) {
+        if (per_replica % q != 0 || (per_replica / q) % 128 != 0) continue;
+        best = q;
+        if (blocks * W * q >= 256) break;
+      }
+      if (best > 0) return W * best;
+    }
+  }
   const int ce = dtype_ce(dt);
   const int bke = 128 / dtype_size(dt);
   int tiles = (Mout <= 64) ? cdiv(Mout, 64) * cdiv(NK + ce, 256) : cdiv(Mout, 128) * cdiv(NK + ce, 128);
-  const int per_replica = P / W;  // pixels of one replica's mini-batch
   int q = cdiv(1024, tiles * W);  // aim at ~1024 workgroups
   int qmax = per_replica / (2 * bke);  // at least two k-tiles per split
   if (qmax < 1) qmax = 1;
   if (q > qmax) q = qmax;
-  if (q * W > 256) q = 256 / W;  // the update kernel walks the splits serially
+  if (q * W > 256) q = 256 / W;
   if (q < 1) q = 1;
   while (q > 1 && per_replica % q != 0) --q;  // splits never straddle replicas
   return W * q;

@@ -89,8 +89,11 @@ struct UpdateDesc {
 
 void launch_conv(int dt, const ConvParams& p, hipStream_t s);
 void launch_wgrad(int dt, const WgradParams& p, hipStream_t s);
-// chooses the split count of the pixel reduction for a wgrad problem (multiple of W)
-int wgrad_choose_split(int dt, int Mout, int NK, int P, int W);
+// Chooses the split count of the pixel reduction for a wgrad problem: a multiple of the replica
+// count W, so that no split mixes two replicas. shape: every field that describes the layer
+// (Nimg, H, W, Cx, Ho, Wo, Mout, ldy, R, S, stride, pad, NK, P, zeros non-null); nsplit,
+// pix_per_split and the pointers are ignored.
+int wgrad_choose_split(int dt, const WgradParams& shape, int W);
 
 void launch_ingest(int dt, const IngestParams& p, hipStream_t s);
 void launch_maxpool_fwd(int dt, const void* x, void* y, int N, int H, int W, int C, hipStream_t s);
