@@ -61,6 +61,8 @@ struct Tensor {
   bool relu_out = false;
   size_t bytes = 0;     // whole mini-batch of all replicas
   size_t ring_off = 0;  // offset inside a ring slot (T_RING)
+  bool has_bits = false;  // a sign plane (one bit per element, > 0) is kept beside the tensor in its ring slot
+  size_t bits_off = 0;
   char* temp = nullptr; // T_TEMP storage
   int grad = G_NONE;    // gradient buffer id
 };
@@ -287,6 +289,7 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
         if (nxt < hi && sp.layers[nxt].op == DDS_OP_RELU) {
           nd.relu = true;
           m.tensors[out].relu_out = true;
+          m.tensors[out].has_bits = !nd.out_f32 && m.tensors[out].Cpad % 8 == 0;
           ++nxt;
         }
         if (have_sc) {
@@ -422,7 +425,11 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
     // ring: R slots of every saved tensor
     size_t off = 0;
     for (Tensor& t : m.tensors)
-      if (t.kind == T_RING) { t.ring_off = off; off = align_up(off + t.bytes, 256); }
+      if (t.kind == T_RING) {
+        t.ring_off = off;
+        off = align_up(off + t.bytes, 256);
+        if (t.has_bits) { t.bits_off = off; off = align_up(off + (size_t)c.N * t.H * t.W * t.Cpad / 8, 256); }
+      }
     m.slot_bytes = off;
     m.ring = A.take(m.slot_bytes * m.R);
     for (Tensor& t : m.tensors)
@@ -463,7 +470,7 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
     int nb_u = 0, nb_s = 0;
     for (ParamLayer& L : m.layers) {
       nb_u += (int)((L.n + 1023) / 1024);
-      if (L.need_stash) nb_s += (int)((L.stash_elems + 1023) / 1024);
+      if (L.need_stash) nb_s += L.RS * ((L.Cin + 63) / 64) * ((L.Coutpad + 63) / 64);  // 64 x 64 tiles per tap
     }
     m.blocks_update = nb_u;
     m.blocks_stash = nb_s;
@@ -558,6 +565,19 @@ char* input_ptr(dds_ctx& c, int k0, int64_t batch) {
   return up.ring + (size_t)slot * up.slot_bytes + up.tensors[up.out_tensor].ring_off;
 }
 
+// sign plane of a tensor in the given ring slot (null if it has none)
+char* bits_ptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
+  const Tensor& t = m.tensors[ti];
+  if (t.kind == T_RING) return t.has_bits ? m.ring + (size_t)slot * m.slot_bytes + t.bits_off : nullptr;
+  if (t.kind == T_EXTERNAL) {
+    Module& up = c.mods[m.k0 - 1];
+    const Tensor& ut = up.tensors[up.out_tensor];
+    const int uslot = (int)((batch + m.k0 - 1) % up.R);
+    return ut.has_bits ? up.ring + (size_t)uslot * up.slot_bytes + ut.bits_off : nullptr;
+  }
+  return nullptr;
+}
+
 char* tptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
   const Tensor& t = m.tensors[ti];
   if (t.kind == T_TEMP) return t.temp;
@@ -615,6 +635,7 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
         p.bias = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
         p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
         p.mask = nullptr;
+        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
         p.zeros = c.zeros;
         p.Nimg = c.N; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
         p.Ho = to.H; p.Wo = to.W;
@@ -686,7 +707,8 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
           p.y = gin;
           p.bias = nullptr;
           p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
-          p.mask = nd.mask_in ? x : nullptr;
+          p.maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, b) : nullptr;
+          p.mask = nd.mask_in && !p.maskbits ? x : nullptr;
           p.zeros = c.zeros;
           p.Nimg = c.N; p.H = to.H; p.W = to.W; p.Cx = ldg;
           p.Ho = ti.H; p.Wo = ti.W;
@@ -743,7 +765,7 @@ int upload_tables(dds_ctx& c) {
       d.Cout = L.Cout; d.RS = L.RS; d.Cinpad = L.Cinpad; d.Cin = L.Cin; d.Coutpad = L.Coutpad;
       for (int b = 0; b < (int)((L.n + 1023) / 1024); ++b) { mu.push_back((int)li); mu.push_back(b); }
       if (L.need_stash)
-        for (int b = 0; b < (int)((L.stash_elems + 1023) / 1024); ++b) { ms.push_back((int)li); ms.push_back(b); }
+        for (int b = 0; b < L.RS * ((L.Cin + 63) / 64) * ((L.Coutpad + 63) / 64); ++b) { ms.push_back((int)li); ms.push_back(b); }
     }
     if (!descs.empty()) HIP_TRY(hipMemcpy(m.descs_dev, descs.data(), sizeof(UpdateDesc) * descs.size(), hipMemcpyHostToDevice));
     if (!mu.empty()) HIP_TRY(hipMemcpy(m.map_update_dev, mu.data(), sizeof(int) * mu.size(), hipMemcpyHostToDevice));

@@ -138,6 +138,26 @@ __device__ __forceinline__ void positive4(const uint2& t, bool* pos) {
   pos[2] = (int)(t.y << 16) >= 0x10000; pos[3] = (int)t.y >= 0x10000;
 }
 
+// Four bytes of a sign plane row: channels cbase .. cbase+31 of pixel pix (zero where the row ends earlier).
+__device__ __forceinline__ uint32_t load_bits32(const void* bits, size_t pix, int ldy, int cbase, bool valid) {
+  if (!valid || cbase >= ldy) return 0u;
+  const uint8_t* row = (const uint8_t*)bits + pix * (size_t)(ldy >> 3) + (cbase >> 3);
+  if ((ldy & 31) == 0) return *(const uint32_t*)row;
+  uint32_t w = 0;
+  for (int b = 0; b < 4 && cbase + 8 * b < ldy; ++b) w |= (uint32_t)row[b] << (8 * b);
+  return w;
+}
+__device__ __forceinline__ void store_bits32(void* bits, size_t pix, int ldy, int cbase, uint32_t w) {
+  if (cbase >= ldy) return;
+  uint8_t* row = (uint8_t*)bits + pix * (size_t)(ldy >> 3) + (cbase >> 3);
+  if ((ldy & 31) == 0) { *(uint32_t*)row = w; return; }
+  for (int b = 0; b < 4 && cbase + 8 * b < ldy; ++b) row[b] = (uint8_t)(w >> (8 * b));
+}
+// nibble i of x -> bits [8i, 8i+4)
+__device__ __forceinline__ uint32_t spread_nibbles(uint32_t x) {
+  return (x & 0xfu) | ((x & 0xf0u) << 4) | ((x & 0xf00u) << 8) | ((x & 0xf000u) << 12);
+}
+
 // bias values of this lane's channel groups (zero past Nout), read once per kernel
 template <int NJ>
 __device__ __forceinline__ void load_bias_groups(const ConvParams& p, int nb, float (&bias)[NJ][4][4]) {
@@ -161,8 +181,19 @@ template <typename T, int NJ, int NI>
 __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_t (&acc)[NJ][NI], int i, bool valid,
                                               size_t pix, int nb, const float (&bias)[NJ][4][4],
                                               const char DDS_LDS_AS* lds = nullptr, int res_off = -1, int mask_off = -1,
-                                              int tile_row = 0, int row_bytes = 0, int nloc0 = 0, int ab_off = -1) {
+                                              int tile_row = 0, int row_bytes = 0, int nloc0 = 0, int ab_off = -1,
+                                              const uint32_t* mbits = nullptr) {
   typedef typename Raw4<T>::type raw_t;
+  static_assert(NJ <= 2, "the sign words hold 8 nibbles");
+  const int half = (threadIdx.x >> 5) & 1;   // which 4 channels of every 8 this lane holds
+  const int nwave0 = nb - 4 * half;           // first channel of the wave's span
+  // sign planes: word j covers channels nwave0 + 32 j .. + 31, bit 8 g + 4 half + q is this lane's (j, g, q)
+  uint32_t mw[NJ] = {};
+  if (p.maskbits) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) mw[j] = mbits ? mbits[j] : load_bits32(p.maskbits, pix, p.ldy, nwave0 + 32 * j, valid);
+  }
+  uint32_t signs = 0;  // nibble 4 j + g: this lane's four outputs of group (j, g) that are > 0
   size_t o[NJ][4];
   bool ok[NJ][4];
   raw_t r[NJ][4], mk[NJ][4];
@@ -225,11 +256,31 @@ __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_
 #pragma unroll
         for (int q = 0; q < 4; ++q) v[q] = pos[q] ? v[q] : 0.f;
       }
+      if (p.maskbits) {
+        const uint32_t nib = mw[j] >> (8 * g + 4 * half);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = ((nib >> q) & 1u) ? v[q] : 0.f;
+      }
+      if (p.bits_out) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) signs |= (v[q] > 0.f ? 1u : 0u) << (4 * (4 * j + g) + q);
+      }
       if (ok[j][g]) {
         if (p.out_f32) store4<float>(p.y, o[j][g], v);
         else store4<T>(p.y, o[j][g], v);
       }
     }
+  if (p.bits_out) {
+    // the other half of the wave holds the other four channels of every byte
+    const uint32_t other = (uint32_t)__shfl_xor((int)signs, 32, 64);
+    const uint32_t lo = half ? other : signs, hi = half ? signs : other;
+    // half h writes word j = h (both halves hold all nibbles now); with NJ == 1 only half 0 writes
+    const int jw = half;
+    if (jw < NJ && valid) {
+      const uint32_t w = spread_nibbles((lo >> (16 * jw)) & 0xffffu) | (spread_nibbles((hi >> (16 * jw)) & 0xffffu) << 4);
+      store_bits32(p.bits_out, pix, p.ldy, nwave0 + 32 * jw, w);
+    }
+  }
 }
 
 // ------------------------------------------------------------------ forward / dgrad
@@ -733,6 +784,20 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) boff[j][ks] = n * KB + (((2 * ks + half) ^ swz(n)) << 4);
   }
+  // dgrad through a ReLU: the sign bits of this lane's outputs are fetched now (a few bytes per
+  // pixel, the oldest loads of the kernel) so that the epilogue reads nothing but the accumulators
+  uint32_t mb[NI][NJ] = {};
+  if (p.maskbits) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int m = wave_m * WM + i * 32 + lpix;
+      const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
+      const int gi = img0 + im;
+      const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) mb[i][j] = load_bits32(p.maskbits, pix, p.ldy, n0 + wave_n * WN + 32 * j, gi < p.Nimg);
+    }
+  }
 
   f32x16_t acc[NJ][NI];
 #pragma unroll
@@ -849,7 +914,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     const int gi = img0 + im;
     const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
     epilogue_tile<T, NJ, NI>(p, acc, i, gi < p.Nimg, pix, nb, bias, (const char DDS_LDS_AS*)smem, res_off, mask_off, m, ROWB,
-                             wave_n * WN + 4 * (lane >> 5), ab_off);
+                             wave_n * WN + 4 * (lane >> 5), ab_off, mb[i]);
   }
 }
 

@@ -30,6 +30,11 @@ struct ConvParams {
   const float* bias;  // fp32 [Nout] or null
   const void* res;    // same layout as y (dtype T) or null
   const void* mask;   // same layout as y (dtype T) or null
+  // Sign planes of ReLU outputs: [pixel][ldy / 8] bytes, bit c % 8 of byte c / 8 set iff channel c
+  // of the stored tensor is > 0 (needs ldy % 8 == 0). bits_out: written with y by a forward launch
+  // with relu. maskbits: what a dgrad launch multiplies by instead of reading `mask` (the full tensor).
+  void* bits_out;
+  const void* maskbits;
   const void* zeros;  // kZeroBytes zero bytes (source of padding rows for LDS fills)
   int Nimg, H, W, Cx; // gathered tensor: NHWC, channel stride Cx (= GEMM-K per tap)
   int Ho, Wo;         // pixel grid of y; M = Nimg*Ho*Wo

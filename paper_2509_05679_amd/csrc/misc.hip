@@ -321,22 +321,36 @@ __global__ __launch_bounds__(256) void recast_kernel(const UpdateDesc* descs, co
   }
 }
 
-// transposed snapshot: stash[slot][c][tap][kpad] <- master[k][tap][cpad], zero for k >= Cout
+// transposed snapshot: stash[slot][c][tap][kpad] <- master[k][tap][cpad], zero for k >= Cout.
+// One workgroup moves a 64(k) x 64(c) tile of one tap through LDS so that both the reads
+// (64 consecutive c) and the writes (64 consecutive k) are whole cache lines.
+// block_map[2*blk+1] = tile index = (tap * cblocks + cb) * kblocks + kb.
 template <typename T>
 __global__ __launch_bounds__(256) void stash_kernel(const UpdateDesc* descs, const int* block_map, int slot) {
   const UpdateDesc d = descs[block_map[2 * blockIdx.x]];
   if (!d.stash) return;
-  const long long total = (long long)d.Cin * d.RS * d.Coutpad;
-  const long long base = (long long)block_map[2 * blockIdx.x + 1] * 1024 + threadIdx.x * 4;
-  for (long long i = base; i < total && i < base + 4; ++i) {
-    const int k = (int)(i % d.Coutpad);
-    const long long r = i / d.Coutpad;
-    const int tap = (int)(r % d.RS);
-    const int c = (int)(r / d.RS);
-    const float v = k < d.Cout ? d.master[((size_t)k * d.RS + tap) * d.Cinpad + c] : 0.f;
-    const size_t o = (size_t)slot * d.stash_slot_elems + i;
-    if (sizeof(T) == 2) ((uint16_t*)d.stash)[o] = f2bf(v);
-    else ((float*)d.stash)[o] = v;
+  __shared__ float tile[64][65];
+  const int kblocks = (d.Coutpad + 63) / 64, cblocks = (d.Cin + 63) / 64;
+  int t = block_map[2 * blockIdx.x + 1];
+  const int kb = t % kblocks; t /= kblocks;
+  const int cb = t % cblocks;
+  const int tap = t / cblocks;
+  const int ty = threadIdx.x >> 6, tx = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int k = kb * 64 + ty * 16 + i, c = cb * 64 + tx;
+    tile[ty * 16 + i][tx] = (k < d.Cout && c < d.Cinpad) ? d.master[((size_t)k * d.RS + tap) * d.Cinpad + c] : 0.f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int c = cb * 64 + ty * 16 + i, k = kb * 64 + tx;
+    if (c < d.Cin && k < d.Coutpad) {
+      const size_t o = (size_t)slot * d.stash_slot_elems + ((size_t)c * d.RS + tap) * d.Coutpad + k;
+      const float v = tile[tx][ty * 16 + i];
+      if (sizeof(T) == 2) ((uint16_t*)d.stash)[o] = f2bf(v);
+      else ((float*)d.stash)[o] = v;
+    }
   }
 }
 
