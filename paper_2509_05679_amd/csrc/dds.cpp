@@ -89,6 +89,8 @@ struct Node {
   int gout = G_NONE, gin = G_NONE, addend = G_NONE;
   bool mask_in = false;
   bool out_f32 = false;
+  int fold_sc = -1;        // first conv of a projection block: node of the 1x1 shortcut whose dgrad rides in this one's
+  bool dgrad_folded = false;  // shortcut node: no dgrad launch of its own
 };
 
 struct GradBuf {
@@ -411,10 +413,33 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
       if (m.nodes[nj].in == block_in && m.tensors[m.nodes[nj].out].kind != T_TEMP) { first = &m.nodes[nj]; break; }
     if (!first || first->kind != N_CONV) return fail(DDS_EUNSUPPORTED, "a residual block must start with CONV2D");
     if (first == &nd) return fail(DDS_EUNSUPPORTED, "a residual block needs at least two convolutions");
-    if (first->gin != G_NONE) first->addend = shortcut_grad;
+    if (first->gin != G_NONE) {
+      first->addend = shortcut_grad;
+      // A 1x1 stride-2 pad-0 projection beside a stride-2 first conv: its input gradient only reaches
+      // the even pixels and is accumulated inside the first conv's dgrad launch (the stride-2 dgrad
+      // kernel takes it as extra reduction steps) instead of going through a scratch tensor.
+      if (tr.kind == T_TEMP) {
+        Node* sc = nullptr;
+        for (size_t nj = 0; nj < ni; ++nj)
+          if (m.nodes[nj].out == nd.res) sc = &m.nodes[nj];
+        const ParamLayer& Ls = m.layers[sc->layer];
+        const ParamLayer& Lf = m.layers[first->layer];
+        const int bke = 64 / dtype_size(dt);  // k-tile of the generic kernels, in elements
+        const Tensor& tf = m.tensors[first->out];
+        const Tensor& ts = m.tensors[sc->out];
+        if (Ls.R == 1 && Ls.stride == 2 && Ls.pad == 0 && Lf.stride == 2 && tf.H == ts.H && tf.W == ts.W &&
+            tf.Cpad % bke == 0 && ts.Cpad % bke == 0 && sc->gin >= 0) {
+          m.grads[sc->gin].bytes = 0;  // the scratch tensor is not needed
+          sc->gin = G_NONE;
+          sc->dgrad_folded = true;
+          first->addend = G_NONE;
+          first->fold_sc = (int)(sc - &m.nodes[0]);
+        }
+      }
+    }
   }
   for (Node& nd : m.nodes)
-    if (nd.kind == N_CONV && nd.gin != G_NONE) m.layers[nd.layer].need_stash = true;
+    if (nd.kind == N_CONV && (nd.gin != G_NONE || nd.dgrad_folded)) m.layers[nd.layer].need_stash = true;
   return DDS_OK;
 }
 
@@ -707,6 +732,13 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
           p.y = gin;
           p.bias = nullptr;
           p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
+          if (nd.fold_sc >= 0) {
+            const Node& sc = m.nodes[nd.fold_sc];
+            const ParamLayer& Ls = m.layers[sc.layer];
+            p.x2 = gptr(c, m, sc.gout, t);
+            p.w2 = Ls.stash + (size_t)slot * align_up((size_t)Ls.stash_elems * es, 256);
+            p.Cx2 = m.tensors[sc.out].Cpad;
+          }
           p.maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, b) : nullptr;
           p.mask = nd.mask_in && !p.maskbits ? x : nullptr;
           p.zeros = c.zeros;

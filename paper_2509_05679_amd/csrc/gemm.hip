@@ -329,7 +329,7 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int til
     }
   };
 
-  int a_h[AP], a_w[AP];
+  int a_h[AP], a_w[AP], a_img[AP];
   const char* a_base[AP];
   bool a_ok[AP];
 #pragma unroll
@@ -339,15 +339,18 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int til
     int mm = a_ok[i] ? m : 0;
     int img, oh, ow;
     row_pixel(mm, img, oh, ow);
+    a_img[i] = img;
     if (DGRAD) { a_h[i] = oh + p.pad; a_w[i] = ow + p.pad; }
     else { a_h[i] = oh * p.stride - p.pad; a_w[i] = ow * p.stride - p.pad; }
     a_base[i] = (const char*)p.x + (size_t)img * p.H * p.W * p.Cx * ES;
   }
   const char* b_base[BP];
   bool b_ok[BP];
+  int b_n[BP];
 #pragma unroll
   for (int i = 0; i < BP; ++i) {
     int n = n0 + rbase + i * ROWS;
+    b_n[i] = n;
     b_ok[i] = n < p.Nout;
     b_base[i] = (const char*)p.w + (size_t)(b_ok[i] ? n : 0) * p.Ktot * ES;
   }
@@ -388,6 +391,24 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int til
     kc += BKE;
     while (kc >= p.Cx) { kc -= p.Cx; if (++ks == p.S) { ks = 0; ++kr; } }
   };
+  // extra reduction steps of a folded 1x1 stride-2 shortcut (class (0, 0) only): same pixel as the
+  // centre tap, other tensor and weights
+  int k2 = chunk * CE;
+  auto load_global2 = [&]() {
+#pragma unroll
+    for (int i = 0; i < AP; ++i) {
+      const int hi = (a_h[i] - p.pad) >> 1, wi = (a_w[i] - p.pad) >> 1;
+      oka[i] = a_ok[i];
+      const size_t off = oka[i] ? ((size_t)(hi * p.W + wi) * p.Cx2 + k2) * ES : 0;
+      ra[i] = *(const uint4*)((const char*)p.x2 + (size_t)a_img[i] * p.H * p.W * p.Cx2 * ES + off);
+    }
+#pragma unroll
+    for (int i = 0; i < BP; ++i) {
+      okb[i] = b_ok[i];
+      rb[i] = *(const uint4*)((const char*)p.w2 + ((size_t)(b_ok[i] ? b_n[i] : 0) * p.Cx2 + k2) * ES);
+    }
+    k2 += BKE;
+  };
   auto store_lds = [&](int buf) {
     char* As = smem + buf * (BM + BN) * LDK;
     char* Bs = As + BM * LDK;
@@ -424,18 +445,24 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int til
     for (int q = 0; q < p.S; ++q) ns += ((cw + p.pad - q) & 1) == 0;
     nk = nr * ns * tiles_per_tap;
   }
+  const int nk1 = nk;  // k-tiles of the layer itself; the folded shortcut follows
+  if (S2 && p.x2 != nullptr && cls == 0) nk += p.Cx2 / BKE;
+  auto load_tile = [&](int kt) {
+    if (S2 && kt >= nk1) {
+      load_global2();
+    } else {
+      skip_dead_taps();
+      load_global();
+    }
+  };
   if (nk > 0) {
-    skip_dead_taps();
-    load_global();
+    load_tile(0);
     store_lds(0);
   }
   __syncthreads();
   for (int kt = 0; kt < nk; ++kt) {
     const int buf = kt & 1;
-    if (kt + 1 < nk) {
-      skip_dead_taps();
-      load_global();
-    }
+    if (kt + 1 < nk) load_tile(kt + 1);
     const char* As = smem + buf * (BM + BN) * LDK + wave_m * WM * LDK;
     const char* Bs = smem + buf * (BM + BN) * LDK + BM * LDK + wave_n * WN * LDK;
     // weights are the MFMA A operand so that a lane ends up with 4 consecutive output
@@ -1427,7 +1454,8 @@ void launch_conv_t(const ConvParams& p, hipStream_t s) {
     return;
   }
   // dgrad of a stride-2 convolution: workgroups per parity class (class (0,0) is the largest)
-  const bool s2 = p.dgrad && p.stride == 2 && p.Cx % (BKB / (int)sizeof(T)) == 0;
+  const bool s2 = p.dgrad && p.stride == 2 && p.Cx % (BKB / (int)sizeof(T)) == 0 &&
+                  (p.x2 == nullptr || p.Cx2 % (BKB / (int)sizeof(T)) == 0);
   const int mc = p.Nimg * ((p.Ho + 1) / 2) * ((p.Wo + 1) / 2);
   if (p.ldy <= 64) {
     const int tpc = cdiv(mc, 256);
@@ -1519,7 +1547,10 @@ template <typename T>
 void launch_wgrad_t(const WgradParams& p, hipStream_t s) {
   constexpr int CE = 16 / sizeof(T);
   if (sizeof(T) == 2 && launch_wgrad_dma(p, s)) return;
-  if (p.Mout <= 64) {
+  if (p.Mout <= 64 && p.NK + CE <= 128) {  // e.g. the stem: 3 input channels, 9 taps
+    dim3 grid(cdiv(p.Mout, 64), 1, p.nsplit);
+    wgrad_gemm_kernel<T, 64, 128, 32, 64><<<grid, 256, 0, s>>>(p);
+  } else if (p.Mout <= 64) {
     dim3 grid(cdiv(p.Mout, 64), cdiv(p.NK + CE, 256), p.nsplit);
     wgrad_gemm_kernel<T, 64, 256, 64, 64><<<grid, 256, 0, s>>>(p);
   } else {

@@ -35,6 +35,12 @@ struct ConvParams {
   // with relu. maskbits: what a dgrad launch multiplies by instead of reading `mask` (the full tensor).
   void* bits_out;
   const void* maskbits;
+  // dgrad of a stride-2 layer only: gradient of a 1x1 stride-2 pad-0 shortcut that shares this
+  // layer's input, folded in as extra reduction steps. x2: [Nimg][H][W][Cx2] (same pixel grid as x),
+  // w2: [Nout][Cx2]; output pixel (oh, ow) with oh, ow even receives sum_k x2[oh/2, ow/2, k] * w2[n][k].
+  const void* x2;
+  const void* w2;
+  int Cx2;
   const void* zeros;  // kZeroBytes zero bytes (source of padding rows for LDS fills)
   int Nimg, H, W, Cx; // gathered tensor: NHWC, channel stride Cx (= GEMM-K per tap)
   int Ho, Wo;         // pixel grid of y; M = Nimg*Ho*Wo
