@@ -174,30 +174,31 @@ __device__ __forceinline__ void load_bias_groups(const ConvParams& p, int nb, fl
       }
 }
 
-// res_lds / mask_lds: if non-null the tile's residual / mask values were staged in LDS as
+// res_off / mask_off >= 0: the tile's residual / mask values were staged in LDS as
 // [tile row][row_bytes] with 16-byte column c of row m stored at column c ^ (m & (ncol-1));
 // tile_row is this lane's row, ncol = row_bytes / 16, nloc0 the lane's first channel inside the tile.
+// The function is laid out in phases (gather operands, arithmetic, store, sign plane) with one
+// uniform branch per phase at most: every option inside the arithmetic is a select, not a
+// branch, because each branch costs the compiler's conservative waits at its join.
 template <typename T, int NJ, int NI>
 __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_t (&acc)[NJ][NI], int i, bool valid,
                                               size_t pix, int nb, const float (&bias)[NJ][4][4],
                                               const char DDS_LDS_AS* lds = nullptr, int res_off = -1, int mask_off = -1,
                                               int tile_row = 0, int row_bytes = 0, int nloc0 = 0, int ab_off = -1,
-                                              const uint32_t* mbits = nullptr) {
+                                              const uint32_t* mbits = nullptr, int out_off = -1) {
   typedef typename Raw4<T>::type raw_t;
   static_assert(NJ <= 2, "the sign words hold 8 nibbles");
   const int half = (threadIdx.x >> 5) & 1;   // which 4 channels of every 8 this lane holds
   const int nwave0 = nb - 4 * half;           // first channel of the wave's span
-  // sign planes: word j covers channels nwave0 + 32 j .. + 31, bit 8 g + 4 half + q is this lane's (j, g, q)
-  uint32_t mw[NJ] = {};
-  if (p.maskbits) {
-#pragma unroll
-    for (int j = 0; j < NJ; ++j) mw[j] = mbits ? mbits[j] : load_bits32(p.maskbits, pix, p.ldy, nwave0 + 32 * j, valid);
-  }
-  uint32_t signs = 0;  // nibble 4 j + g: this lane's four outputs of group (j, g) that are > 0
+  const int ncolm = (row_bytes >> 4) - 1;
+  // explicit LDS address space: a generic pointer would turn these into flat loads, which
+  // also count as vector-memory operations and would wait for every earlier global store
+  auto lds_at = [&](int base_off, int j, int g) {
+    const int bytecol = (nloc0 + 32 * j + 8 * g) * (int)sizeof(T);
+    return (char DDS_LDS_AS*)lds + base_off + tile_row * row_bytes + ((((bytecol >> 4) ^ tile_row) & ncolm) << 4) + (bytecol & 15);
+  };
   size_t o[NJ][4];
   bool ok[NJ][4];
-  raw_t r[NJ][4], mk[NJ][4];
-  const int ncolm = (row_bytes >> 4) - 1;
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
 #pragma unroll
@@ -206,70 +207,97 @@ __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_
       ok[j][g] = valid && n < p.ldy;
       o[j][g] = ok[j][g] ? pix * p.ldy + n : 0;
     }
-  // explicit LDS address space: a generic pointer would turn these into flat loads, which
-  // also count as vector-memory operations and would wait for every earlier global store
-  auto lds_at = [&](int base_off, int j, int g) {
-    const int bytecol = (nloc0 + 32 * j + 8 * g) * (int)sizeof(T);
-    return lds + base_off + tile_row * row_bytes + ((((bytecol >> 4) ^ tile_row) & ncolm) << 4) + (bytecol & 15);
-  };
-  if (p.res) {
+
+  uint32_t signs = 0;  // nibble 4 j + g: this lane's four outputs of group (j, g) that are > 0
+  const float lower = p.relu ? 0.f : -__builtin_inff();
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
+  for (int j = 0; j < NJ; ++j) {  // one 32-channel tile at a time keeps the temporaries at 16 registers each
+    // ---- gather: alpha * bias, residual, mask (defaults: 0, 0, keep everything)
+    float ab[4][4], rs[4][4];
+    uint32_t keep = 0xffffffffu;  // bit 8 g + 4 half + q: output (g, q) survives the mask
+    if (ab_off >= 0) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const uint4 t = lds_load<uint4>(lds + ab_off + (nloc0 + 32 * j + 8 * g) * 4);
+        ab[g][0] = __uint_as_float(t.x); ab[g][1] = __uint_as_float(t.y);
+        ab[g][2] = __uint_as_float(t.z); ab[g][3] = __uint_as_float(t.w);
+      }
+    } else {
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        r[j][g] = res_off >= 0 ? lds_load<raw_t>(lds_at(res_off, j, g)) : *(const raw_t*)((const T*)p.res + o[j][g]);
-  }
-  if (p.mask) {
 #pragma unroll
-    for (int j = 0; j < NJ; ++j)
+        for (int q = 0; q < 4; ++q) ab[g][q] = p.alpha * bias[j][g][q];
+    }
+    if (res_off >= 0) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) unpack4(lds_load<raw_t>(lds_at(res_off, j, g)), rs[g]);
+    } else if (p.res) {
+      raw_t r[4];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) r[g] = *(const raw_t*)((const T*)p.res + o[j][g]);
+#pragma unroll
+      for (int g = 0; g < 4; ++g) unpack4(r[g], rs[g]);
+    } else {
 #pragma unroll
       for (int g = 0; g < 4; ++g)
-        mk[j][g] = mask_off >= 0 ? lds_load<raw_t>(lds_at(mask_off, j, g)) : *(const raw_t*)((const T*)p.mask + o[j][g]);
-  }
 #pragma unroll
-  for (int j = 0; j < NJ; ++j)
+        for (int q = 0; q < 4; ++q) rs[g][q] = 0.f;
+    }
+    if (p.maskbits) {
+      keep = mbits ? mbits[j] : load_bits32(p.maskbits, pix, p.ldy, nwave0 + 32 * j, valid);
+    } else if (p.mask) {
+      raw_t mk[4];
 #pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      float v[4];
-      if (ab_off >= 0) {  // alpha * bias staged in LDS: no global load (and no wait on earlier stores) in this loop
-        const uint4 abr = lds_load<uint4>(lds + ab_off + (nloc0 + 32 * j + 8 * g) * 4);
-        const float4 ab = make_float4(__uint_as_float(abr.x), __uint_as_float(abr.y), __uint_as_float(abr.z), __uint_as_float(abr.w));
-        v[0] = fmaf(p.alpha, acc[j][i][4 * g + 0], ab.x); v[1] = fmaf(p.alpha, acc[j][i][4 * g + 1], ab.y);
-        v[2] = fmaf(p.alpha, acc[j][i][4 * g + 2], ab.z); v[3] = fmaf(p.alpha, acc[j][i][4 * g + 3], ab.w);
-      } else {
+      for (int g = 0; g < 4; ++g)
+        mk[g] = mask_off >= 0 ? lds_load<raw_t>(lds_at(mask_off, j, g)) : *(const raw_t*)((const T*)p.mask + o[j][g]);
+      keep = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = p.alpha * (acc[j][i][4 * g + q] + bias[j][g][q]);
-      }
-      if (p.res) {
-        float t[4];
-        unpack4(r[j][g], t);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] += t[q];
-      }
-      if (p.relu) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = __builtin_amdgcn_fmed3f(v[q], 0.f, __builtin_inff());  // one instruction; NaN -> 0
-      }
-      if (p.mask) {
+      for (int g = 0; g < 4; ++g) {
         bool pos[4];
-        positive4(mk[j][g], pos);
+        positive4(mk[g], pos);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = pos[q] ? v[q] : 0.f;
-      }
-      if (p.maskbits) {
-        const uint32_t nib = mw[j] >> (8 * g + 4 * half);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = ((nib >> q) & 1u) ? v[q] : 0.f;
-      }
-      if (p.bits_out) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) signs |= (v[q] > 0.f ? 1u : 0u) << (4 * (4 * j + g) + q);
-      }
-      if (ok[j][g]) {
-        if (p.out_f32) store4<float>(p.y, o[j][g], v);
-        else store4<T>(p.y, o[j][g], v);
+        for (int q = 0; q < 4; ++q) keep |= (pos[q] ? 1u : 0u) << (8 * g + 4 * half + q);
       }
     }
+
+    // ---- arithmetic: v = alpha * acc + alpha * bias + res, clamp below at 0 (ReLU) or -inf, apply the mask
+    float v[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float t = fmaf(p.alpha, acc[j][i][4 * g + q], ab[g][q]) + rs[g][q];
+        t = __builtin_amdgcn_fmed3f(t, lower, __builtin_inff());  // one instruction; NaN -> lower
+        v[g][q] = ((keep >> (8 * g + 4 * half + q)) & 1u) ? t : 0.f;
+        signs |= (v[g][q] > 0.f ? 1u : 0u) << (4 * (4 * j + g) + q);
+      }
+
+    // ---- store: into the LDS output tile (same layout as the staged residual tile, possibly the very
+    // same bytes: this lane has read its residual values from them already; the workgroup writes the
+    // tile out afterwards in whole rows), or straight to global memory
+    if (out_off >= 0) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        if (sizeof(T) == 2) {
+          u32x2_t t = {pack_bf16(v[g][0], v[g][1]), pack_bf16(v[g][2], v[g][3])};
+          *(u32x2_t DDS_LDS_AS*)(lds_at(out_off, j, g)) = t;
+        } else {
+          u32x4_t t = {__float_as_uint(v[g][0]), __float_as_uint(v[g][1]), __float_as_uint(v[g][2]), __float_as_uint(v[g][3])};
+          *(u32x4_t DDS_LDS_AS*)(lds_at(out_off, j, g)) = t;
+        }
+      }
+    } else if (p.out_f32) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (ok[j][g]) store4<float>(p.y, o[j][g], v[g]);
+    } else {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+        if (ok[j][g]) store4<T>(p.y, o[j][g], v[g]);
+    }
+  }
+
+  // ---- sign plane of the stored values
   if (p.bits_out) {
     // the other half of the wave holds the other four channels of every byte
     const uint32_t other = (uint32_t)__shfl_xor((int)signs, 32, 64);
@@ -897,7 +925,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   constexpr int NCOL = ROWB / 16;      // 16-byte columns per row
   constexpr int RPF = 64 / NCOL;       // rows per wave fill
   constexpr int FPW = BM / RPF / 4;    // fills per wave
-  int res_off = -1, mask_off = -1;
+  int res_off = -1, mask_off = -1, nregions = 0;
   const int ab_off = (int)(lds_dump - lds0);  // the dump block now holds alpha * bias of this tile's channels
   float* ab_lds = (float*)(smem + ab_off);
   wg_barrier();
@@ -929,7 +957,11 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     if (p.mask) mask_off = stage_tile(p.mask);
     if (p.res) res_off = stage_tile(p.res);
     wait_vm<0>();
+    nregions = region;
   }
+  // Output tile in LDS: the residual tile's bytes if there is one, else the next free region.
+  int out_off = res_off >= 0 ? res_off : ((nregions + 1) * BM * ROWB <= dg.smem_bytes - 1024 ? nregions * BM * ROWB : -1);
+  if (p.out_f32) out_off = -1;
   __syncthreads();  // also orders the plain LDS stores of alpha * bias
 
   const int nb = n0 + wave_n * WN + 4 * (lane >> 5);
@@ -941,7 +973,27 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     const int gi = img0 + im;
     const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
     epilogue_tile<T, NJ, NI>(p, acc, i, gi < p.Nimg, pix, nb, bias, (const char DDS_LDS_AS*)smem, res_off, mask_off, m, ROWB,
-                             wave_n * WN + 4 * (lane >> 5), ab_off, mb[i]);
+                             wave_n * WN + 4 * (lane >> 5), ab_off, mb[i], out_off);
+  }
+  if (out_off >= 0) {
+    // write the tile out: a wave stores RPF whole tile rows per instruction, 16 bytes per lane
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < FPW; ++u) {
+      const int f = wave + 4 * u;
+      const int row = f * RPF + lane / NCOL, slot = lane % NCOL;
+      const int gc = (slot ^ row) & (NCOL - 1);
+      const int x = row & TWm, y = (row >> g.tw_log) & THm, im = row >> (g.tw_log + g.th_log);
+      const int gi = img0 + im;
+      const int n = n0 + gc * (16 / ES);
+      const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
+      const u32x4_t v = *(const u32x4_t DDS_LDS_AS*)((const char DDS_LDS_AS*)smem + out_off + f * 1024 + lane * 16);
+#ifdef DDS_NT_STORE
+      if (gi < p.Nimg && n < p.ldy) __builtin_nontemporal_store(v, (u32x4_t*)((char*)p.y + (pix * p.ldy + n) * ES));
+#else
+      if (gi < p.Nimg && n < p.ldy) *(u32x4_t*)((char*)p.y + (pix * p.ldy + n) * ES) = v;
+#endif
+    }
   }
 }
 
