@@ -811,10 +811,31 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     for (int u = 0; u < WL; ++u) dma16s(base, wvo[u], lds_wring + slot * (BN * KB) + (wave + 4 * u) * 1024);
   };
 
-  // fragment addressing
   // pixel of the 32-pixel fragment held by this lane: quads {0,3,5,6} -> pixels 0..15, {1,2,4,7} -> 16..31
   const int lq = (lane >> 2) & 7;
   const int lpix = ((__builtin_popcount(lq) & 1) << 4) | ((lq >> 1) << 2) | (lane & 3);
+  // dgrad through a ReLU: the sign bits of this lane's outputs are fetched now (a few bytes per
+  // pixel, the oldest loads of the kernel) so that the epilogue reads nothing but the accumulators
+  uint32_t mb[NI][NJ] = {};
+  if (p.maskbits) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int m = wave_m * WM + i * 32 + lpix;
+      const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
+      const int gi = img0 + im;
+      const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) mb[i][j] = load_bits32(p.maskbits, pix, p.ldy, n0 + wave_n * WN + 32 * j, gi < p.Nimg);
+    }
+  }
+
+  // prologue: whole first patch, then the weight tiles of stages 0 and 1. Issued before the rest of
+  // the set-up (fragment addresses, sign words, accumulators) so that it runs under the copies' latency.
+  for (int j = 0; wave + 4 * j < pw_total; ++j) dma16(patch_src(j), patch_dst(j, 0));
+  fill_w(0, 0, 0);
+  fill_w(0, 1, 1);
+
+  // fragment addressing
   const int half = lane >> 5;
   // Patch operand: LDS byte offset of a fragment row = row * KB + (((2 ks + half) ^ f) << 4) with
   // f = fx(x + tap_s) | fy(y + tap_r). Per lane and tap coordinate the swizzle bits are kept in
@@ -839,21 +860,6 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) boff[j][ks] = n * KB + (((2 * ks + half) ^ swz(n)) << 4);
   }
-  // dgrad through a ReLU: the sign bits of this lane's outputs are fetched now (a few bytes per
-  // pixel, the oldest loads of the kernel) so that the epilogue reads nothing but the accumulators
-  uint32_t mb[NI][NJ] = {};
-  if (p.maskbits) {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int m = wave_m * WM + i * 32 + lpix;
-      const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
-      const int gi = img0 + im;
-      const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) mb[i][j] = load_bits32(p.maskbits, pix, p.ldy, n0 + wave_n * WN + 32 * j, gi < p.Nimg);
-    }
-  }
-
   f32x16_t acc[NJ][NI];
 #pragma unroll
   for (int j = 0; j < NJ; ++j)
@@ -861,11 +867,6 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     for (int i = 0; i < NI; ++i)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
-
-  // prologue: whole first patch, then the weight tiles of stages 0 and 1
-  for (int j = 0; wave + 4 * j < pw_total; ++j) dma16(patch_src(j), patch_dst(j, 0));
-  fill_w(0, 0, 0);
-  fill_w(0, 1, 1);
 
   const int pbuf_off = dg.tab_bytes;
   auto compute = [&](int chunk, int tap_r, int tap_s, int slot) {
@@ -1390,6 +1391,10 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
     }
   };
 
+  // the first two tiles are requested before the rest of the set-up, which runs under their latency
+  fill_tile(0, 0);
+  fill_tile(1, 1);
+
   // fragment addressing (see lds_tr16): lane -> (16-lane group, row inside the 4-row block, 8-byte segment)
   const int lq = lane & 15, grp16 = (lane >> 4) & 1, khalf = lane >> 5;
   const int rsub = lq >> 2, seg = lq & 3;
@@ -1432,8 +1437,6 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
   for (int e = 0; e < 16; ++e) accb[e] = 0.f;
   const uint4 ones = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
 
-  fill_tile(0, 0);
-  fill_tile(1, 1);
   for (int t = 0; t < ntiles; ++t) {
     wait_vm<NF>();  // everything but the youngest tile's fills has landed
     wg_barrier();
