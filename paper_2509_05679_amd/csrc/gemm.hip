@@ -1317,15 +1317,20 @@ __device__ __forceinline__ uint2 lds_tr16_at(uint32_t lds_byte_address) {
   return __builtin_bit_cast(uint2, v);
 }
 
+// Waves: four per tap group, each owning a 32(k) x 32(c) quarter of the block. Stride 1 runs
+// three tap groups (one per kernel row, 12 waves, three per SIMD) so that the LDS reads of one wave
+// hide behind the MFMAs of the others; a group's row shift is folded into its lanes' base addresses.
 template <int TWLOG, int THLOG, bool S2>
-__global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradGeom wg, const void* zeros) {
+__global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p, WgradGeom wg, const void* zeros) {
   constexpr int TW = 1 << TWLOG, TH = 1 << THLOG, PW = TW + 2, PP = (TH + 2) * PW;
   constexpr int IMGS = 128 / (TW * TH);
   static_assert(IMGS >= 1 && IMGS * TW * TH == 128, "a tile is 128 pixels");
+  constexpr int NWV = S2 ? 4 : 12;                // waves per workgroup
   constexpr int PROW = (IMGS * PP + 7) / 8 * 8;   // patch rows, whole 8-row fills
-  constexpr int PF = (PROW / 8 + 3) / 4;          // patch fills per wave
-  constexpr int NF = 4 + PF;  // fills per lane per tile: 4 (dY) + PF (patch; surplus ones go to a dump block)
-  constexpr int NT = S2 ? 4 : 9;                  // accumulated taps
+  constexpr int FY = (16 + NWV - 1) / NWV;        // dY fills per wave (16 per tile)
+  constexpr int PF = (PROW / 8 + NWV - 1) / NWV;  // patch fills per wave
+  constexpr int NF = FY + PF;  // fills per lane per tile (surplus ones go to a dump block)
+  constexpr int NT = S2 ? 4 : 3;                  // taps accumulated by one wave
   constexpr int SLOT = 16384 + PROW * 128;
   extern __shared__ __align__(16) char smem[];
   const uint32_t lds_ring = (uint32_t)(size_t)(DDS_LDS_AS char*)smem;
@@ -1333,7 +1338,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wave_m = wave & 1, wave_n = wave >> 1;
+  const int wave_m = wave & 1, wave_n = (wave >> 1) & 1;
+  const int tg = wave >> 2;  // tap group: kernel row of this wave's three taps (stride 1)
   const int k0 = blockIdx.x * 64, z = blockIdx.z;
   const int sub = S2 ? wg.sub[blockIdx.y / wg.cblocks] : 0;
   const int sdy = sub >> 1, sdx = sub & 1;
@@ -1357,7 +1363,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
   int prel[PF], pflag[PF];  // byte offset from the tile origin; yy | column valid << 8
 #pragma unroll
   for (int u = 0; u < PF; ++u) {
-    const int row = (wave + 4 * u) * 8 + l8;
+    const int row = (wave + NWV * u) * 8 + l8;
     int rel = 0, flag = 0;
     if (row < IMGS * PP) {
       const int im = row / PP, rem = row - im * PP;
@@ -1379,11 +1385,13 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
     const char* xsrc = xsrc0 + (size_t)tt * tile_xbytes;
     const bool yok = live_t && ycol_ok;
 #pragma unroll
-    for (int u = 0; u < 4; ++u)  // dY rows: tile pixel 8*(wave+4u) + l8
-      dma16(yok ? ysrc + (size_t)u * 32 * ybytes : zsrc, live_t ? base + (wave + 4 * u) * 1024 : lds_dump);
+    for (int u = 0; u < FY; ++u) {  // dY rows: tile pixel 8*(wave + NWV u) + l8
+      const bool live = live_t && wave + NWV * u < 16;
+      dma16(yok && live ? ysrc + (size_t)u * (NWV * 8) * ybytes : zsrc, live ? base + (wave + NWV * u) * 1024 : lds_dump);
+    }
 #pragma unroll
     for (int u = 0; u < PF; ++u) {  // patch rows
-      const int wl = wave + 4 * u;
+      const int wl = wave + NWV * u;
       const bool live = live_t && wl < pw_total;
       const int gh = h0 + (pflag[u] & 255) - 1;
       const bool ok = live && (pflag[u] >> 8) && (unsigned)gh < (unsigned)p.Ho;
@@ -1410,7 +1418,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     const int ql = 8 * khalf + rsub + 4 * hh;
-    const int rl = (ql >> TWLOG) * PW + (ql & (TW - 1));
+    const int rl = (ql >> TWLOG) * PW + (ql & (TW - 1)) + (S2 ? 0 : tg * PW);
 #pragma unroll
     for (int v = 0; v < 4; ++v) baddr[hh][v] = rl * 128 + ((b_c ^ (((rl + v) & 3) << 1)) << 4) + 8 * (seg & 1);
   }
@@ -1424,7 +1432,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
       tapreal[t] = rr * p.S + ss;
     } else {
       live[t] = true;
-      tapreal[t] = t;
+      tapreal[t] = tg * 3 + t;
     }
   }
 
@@ -1453,27 +1461,32 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
         asm volatile("" : "+v"(bp[hh][v]));
       }
     asm volatile("" : "+v"(ybuf));
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {  // 16 pixels per step
-      constexpr int dummy = 0; (void)dummy;
+    // Fragments of k-step ks + 1 (16 pixels each) are read into the other register set while the
+    // MFMAs of k-step ks run, so only the first k-step of a tile waits for LDS.
+    uint4 af[2], bf[2][NT];
+    auto load_frags = [&](int ks, int set) {  // ks is a constant after unrolling
       const int q0 = ks * 16;
-      const int rc = (q0 >> (TWLOG + THLOG)) * PP + ((q0 >> TWLOG) & (TH - 1)) * PW + (q0 & (TW - 1));  // compile-time after unrolling
-      uint2 a0 = lds_tr16_at(ybuf + ks * 2048);
-      uint2 a1 = lds_tr16_at(ybuf + ks * 2048 + 512);
-      const uint4 af = make_uint4(a0.x, a0.y, a1.x, a1.y);
+      const int rc = (q0 >> (TWLOG + THLOG)) * PP + ((q0 >> TWLOG) & (TH - 1)) * PW + (q0 & (TW - 1));
+      const uint2 a0 = lds_tr16_at(ybuf + ks * 2048);
+      const uint2 a1 = lds_tr16_at(ybuf + ks * 2048 + 512);
+      af[set] = make_uint4(a0.x, a0.y, a1.x, a1.y);
 #pragma unroll
       for (int tap = 0; tap < NT; ++tap) {
-        const int toff = S2 ? (tap >> 1) * PW + (tap & 1) : (tap / 3) * PW + tap % 3;
+        const int toff = S2 ? (tap >> 1) * PW + (tap & 1) : tap;  // stride 1: the row shift sits in the base
         const int v = (rc + toff) & 3;
-        if (!S2 || live[tap]) {
-          uint2 b0 = lds_tr16_at(bp[0][v] + (rc + toff) * 128);
-          uint2 b1 = lds_tr16_at(bp[1][v] + (rc + toff) * 128);
-          const uint4 bf = make_uint4(b0.x, b0.y, b1.x, b1.y);
-          mfma16B<bf16_t>(af, bf, acc[tap]);
-        }
+        const uint2 b0 = lds_tr16_at(bp[0][v] + (rc + toff) * 128);
+        const uint2 b1 = lds_tr16_at(bp[1][v] + (rc + toff) * 128);
+        bf[set][tap] = make_uint4(b0.x, b0.y, b1.x, b1.y);
       }
-      if (wave_n == 0 && blockIdx.y == 0) mfma16B<bf16_t>(af, ones, accb);  // bias gradient: column sums of dY
-      __builtin_amdgcn_sched_barrier(0);  // keep the reads of later k-steps from being hoisted (register pressure)
+    };
+    load_frags(0, 0);
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      if (ks + 1 < 8) load_frags(ks + 1, (ks + 1) & 1);
+#pragma unroll
+      for (int tap = 0; tap < NT; ++tap)
+        if (!S2 || live[tap]) mfma16B<bf16_t>(af[ks & 1], bf[ks & 1][tap], acc[tap]);
+      if (wave_n == 0 && blockIdx.y == 0 && tg == (S2 ? 0 : 1)) mfma16B<bf16_t>(af[ks & 1], ones, accb);  // bias gradient: column sums of dY
     }
   }
   wait_vm<0>();
@@ -1489,7 +1502,7 @@ __global__ __launch_bounds__(256, 2) void wgrad_dma_kernel(WgradParams p, WgradG
       for (int tap = 0; tap < NT; ++tap)
         if (live[tap]) out[(size_t)k * p.NK + tapreal[tap] * p.Cx + cin] = p.alpha * acc[tap][e];
     }
-    if (wave_n == 0 && (lane & 31) == 0 && blockIdx.y == 0) out[(size_t)p.Mout * p.NK + k] = p.alpha * accb[e];
+    if (wave_n == 0 && (lane & 31) == 0 && blockIdx.y == 0 && tg == (S2 ? 0 : 1)) out[(size_t)p.Mout * p.NK + k] = p.alpha * accb[e];
   }
 }
 
@@ -1538,7 +1551,7 @@ void launch_wgrad_dma_inst(const WgradParams& p, const WgradGeom& wg, int nsub, 
   }
   const int smem = 3 * (16384 + PROW * 128) + 1024;
   dim3 grid(cdiv(p.Mout, 64), nsub * wg.cblocks, p.nsplit);
-  wgrad_dma_kernel<TWLOG, THLOG, S2><<<grid, 256, smem, s>>>(p, wg, p.zeros);
+  wgrad_dma_kernel<TWLOG, THLOG, S2><<<grid, S2 ? 256 : 768, smem, s>>>(p, wg, p.zeros);
 }
 
 // bf16 problems whose splits are whole 128-pixel tiles go to the asynchronous kernel: 3x3
