@@ -143,7 +143,10 @@ double dds_gemm_flops_per_step(const dds_ctx* ctx);
 /* Per-launch timing of the MFMA kernels for the benchmark's roofline record. While
  * enabled every conv/linear forward, dgrad and wgrad launch is bracketed by HIP events on
  * the stream it is launched on and dds_step synchronises at its end (do not time
- * throughput in this mode). dds_profile(ctx, 1) also clears the totals.
+ * throughput in this mode). enable = 1: modules stay on their concurrent streams, so a
+ * launch's duration includes the time it shares the chip with other modules' kernels;
+ * enable = 2: modules run one after another on the caller's stream, so every launch has
+ * the chip to itself; 0: off. Enabling also clears the totals.
  * dds_profile_read fills 9 doubles: for class 0 forward, 1 dgrad, 2 wgrad:
  * summed milliseconds, number of launches, summed algorithmic FLOPs (2*M*N*K). */
 int dds_profile(dds_ctx* ctx, int enable);

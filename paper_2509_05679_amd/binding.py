@@ -195,8 +195,9 @@ class Trainer:
     def dds_gemm_flops_per_step(self) -> float:
         return float(lib.dds_gemm_flops_per_step(self.ctx))
 
-    def dds_profile(self, enable: bool):
-        _check(lib.dds_profile(self.ctx, 1 if enable else 0))
+    def dds_profile(self, enable):
+        """0 / False: off; 1 / True: time launches on their concurrent streams; 2: modules serialised."""
+        _check(lib.dds_profile(self.ctx, int(enable)))
 
     def dds_profile_read(self):
         """{class: (ms, launches, flops)} for forward / dgrad / wgrad launches."""

@@ -160,6 +160,7 @@ struct dds_ctx {
                         // caller's stream (per-kernel timing without other modules sharing the chip)
   // optional per-launch timing of the MFMA kernels (events on the launching stream)
   bool profiling = false;
+  bool profile_serial = false;  // dds_profile(ctx, 2): modules run one after another while profiling
   struct ProfRec { int cls; double flops; hipEvent_t a, b; };
   std::vector<ProfRec> prof_pending;
   std::vector<hipEvent_t> prof_pool;
@@ -975,7 +976,7 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
     launch_ingest(c->dt, p, us);
     ++c->launches;
   }
-  const bool multi = c->K > 1 && !c->serial;
+  const bool multi = c->K > 1 && !c->serial && !c->profile_serial;
   if (multi) HIP_TRY(hipEventRecord(c->fork, us));
   for (int k0 = 0; k0 < c->K; ++k0) {
     Module& m = c->mods[k0];
@@ -1037,6 +1038,7 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
 int dds_profile(dds_ctx* c, int enable) {
   if (!c) return fail(DDS_EINVAL, "null ctx");
   c->profiling = enable != 0;
+  c->profile_serial = enable == 2;
   for (int i = 0; i < 3; ++i) { c->prof_ms[i] = 0; c->prof_flops[i] = 0; c->prof_count[i] = 0; }
   return DDS_OK;
 }
