@@ -782,12 +782,26 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   const uint32_t lds_dump = lds_wring + 3 * (BN * KB);  // 1 KiB that absorbs surplus fills
   // Source of this lane's 16 bytes in the j-th patch fill of this wave, for channel chunk 0.
   // Rows outside the image and surplus fills read the zero block.
-  auto patch_src = [&](int j) -> const char* {
-    const int wl = wave + 4 * j;
-    const bool live = wl < pw_total;  // wave-uniform
-    const int off = tab[(live ? wl * FROWS : 0) + l8];  // pixel * CPR + f, or -1
-    return live && off >= 0 ? (const char*)p.x + (size_t)(off >> FB) * pixbytes + ((pcol ^ (off & (CPR - 1))) << 4) : zsrc;
-  };
+  // (table entries are read in one batch and turned into addresses with selects: a branch per
+  // entry would serialise one LDS round trip per fill at the very start of the kernel)
+  constexpr int NPRO = 7;  // fills per wave that cover the largest patch (4 waves x 7 x FROWS rows)
+  const char* pro_src[NPRO];
+  {
+    int offs[NPRO];
+#pragma unroll
+    for (int j = 0; j < NPRO; ++j) {
+      const int wl = wave + 4 * j;
+      offs[j] = tab[(wl < pw_total ? wl * FROWS : 0) + l8];  // pixel * CPR + f, or -1
+    }
+#pragma unroll
+    for (int j = 0; j < NPRO; ++j) {
+      const bool ok = wave + 4 * j < pw_total && offs[j] >= 0;
+      const int o = ok ? offs[j] : 0;
+      const char* a = (const char*)p.x + (size_t)(o >> FB) * pixbytes + ((pcol ^ (o & (CPR - 1))) << 4);
+      pro_src[j] = ok ? a : zsrc;
+    }
+  }
+  auto patch_src = [&](int j) -> const char* { return pro_src[j]; };
   auto patch_dst = [&](int j, int buf) {
     const int wl = wave + 4 * j;
     return wl < pw_total ? lds_pbuf + buf * pbuf_bytes + wl * 1024 : lds_dump;
@@ -831,7 +845,9 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
 
   // prologue: whole first patch, then the weight tiles of stages 0 and 1. Issued before the rest of
   // the set-up (fragment addresses, sign words, accumulators) so that it runs under the copies' latency.
-  for (int j = 0; wave + 4 * j < pw_total; ++j) dma16(patch_src(j), patch_dst(j, 0));
+#pragma unroll
+  for (int j = 0; j < NPRO; ++j)
+    if (wave + 4 * j < pw_total) dma16(pro_src[j], patch_dst(j, 0));
   fill_w(0, 0, 0);
   fill_w(0, 1, 1);
 
@@ -1044,6 +1060,7 @@ bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
   const int fills_per_wave = (dg.patch_rows / FROWS + 3) / 4;
   if (p.Cx * (int)sizeof(T) % KB != 0) return false;
   const int nchunks = p.Cx * (int)sizeof(T) / KB;
+  if (fills_per_wave > 7) return false;  // the kernel keeps seven prologue sources per lane
   if (PS == 0 ? nchunks != 1 : (nchunks < 2 || 7 * PS < fills_per_wave)) return false;
   const int smem = dg.tab_bytes + (PS > 0 ? 2 : 1) * dg.patch_rows * KB + 3 * BN * KB + 1024;
   if (smem > 160 * 1024 || p.zeros == nullptr) return false;
