@@ -53,7 +53,7 @@ def cpu_baseline(wl, seconds_budget=20.0):
     from dds_inputs import make_batch, make_params, workload
     from oracle import fdg
     small_b = {"cfg0_mlp": wl.B, "cfg1_cnn": 8, "cfg2_resnet18": 2, "cfg3_resnet56": 2, "cfg4_resnet34w": 1}.get(wl.name, 2)
-    small = workload(wl.name, B=small_b) if wl.name.startswith("cfg") else wl
+    small = workload(wl.name, B=small_b)
     pipe = fdg.Pipeline(small.ops, small.bounds, small.W, make_params(small, 0), small.lr, small.momentum)
     pipe.keep_history = False
     warm = 2 * (small.K - 1)

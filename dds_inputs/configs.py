@@ -102,7 +102,7 @@ def _cnn():
     )
 
 
-def _resnet(name, stem, stages, module_blocks, K, W, B, steps):
+def _resnet(name, stem, stages, module_blocks, K, W, B, steps, lr=0.01):
     """stages: list of (channels, n_blocks); module_blocks: blocks per module (len K)."""
     nblocks = sum(n for _, n in stages)
     assert sum(module_blocks) == nblocks and len(module_blocks) == K
@@ -126,7 +126,7 @@ def _resnet(name, stem, stages, module_blocks, K, W, B, steps):
     bounds.append(len(ops))
     return Workload(
         name=name, ops=ops, bounds=bounds, K=K, W=W, B=B, in_shape=(3, 32, 32), classes=10,
-        precision="bf16", lr=0.01, momentum=0.0, steps=steps,
+        precision="bf16", lr=lr, momentum=0.0, steps=steps,
         extra={"blocks": nblocks, "res_scale": scale},
     )
 
@@ -148,14 +148,27 @@ def _resnet34w():
                    [2] * 8, K=8, W=8, B=256, steps=24)
 
 
+def _paper_resnet20(S, K):
+    """The network and batch of the paper's experiments (Section 5: ResNet-20, mini-batch 194 per
+    data-group, S in {1, 4} data-groups, K in {1, 2} modules), BatchNorm-free like cfg2-4, on
+    synthetic CIFAR-shaped data. K = 2 cuts after the fifth of the nine blocks."""
+    return _resnet(f"paper_r20_S{S}K{K}", 16, [(16, 3), (32, 3), (64, 3)], [9] if K == 1 else [5, 4],
+                   K=K, W=S, B=194, steps=2 * (K - 1) + 10)
+
+
 _BUILDERS = {
     "cfg0_mlp": _mlp,
     "cfg1_cnn": _cnn,
     "cfg2_resnet18": _resnet18,
     "cfg3_resnet56": _resnet56,
     "cfg4_resnet34w": _resnet34w,
+    "paper_r20_S1K1": lambda: _paper_resnet20(1, 1),
+    "paper_r20_S1K2": lambda: _paper_resnet20(1, 2),
+    "paper_r20_S4K1": lambda: _paper_resnet20(4, 1),
+    "paper_r20_S4K2": lambda: _paper_resnet20(4, 2),
 }
-WORKLOAD_NAMES = tuple(_BUILDERS)
+WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("cfg"))  # the five benchmark configurations
+PAPER_WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("paper_"))
 
 
 def workload(name: str, *, B: Optional[int] = None, W: Optional[int] = None,

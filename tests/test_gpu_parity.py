@@ -117,6 +117,15 @@ def test_cfg3_resnet56_reduced_batch_bf16():
     _compare(wl, seed=0, T=2 * (wl.K - 1) + 6)
 
 
+def test_paper_resnet20_shapes_reduced_batch_bf16():
+    # The paper's own experiment shapes (Section 5): ResNet-20, S = 4 data-groups, K = 2 modules and
+    # the centralised K = 1 special case; per-group batch 7 (odd, like the paper's 194: ragged tiles).
+    wl = workload("paper_r20_S4K2", B=7)
+    _compare(wl, seed=2, T=wl.steps)
+    wl = workload("paper_r20_S1K1", B=7)
+    _compare(wl, seed=3, T=6)
+
+
 def test_cfg4_resnet34w_reduced_batch_bf16():
     wl = workload("cfg4_resnet34w", B=1, W=4)
     _compare(wl, seed=0, T=2 * (wl.K - 1) + 3)

@@ -62,6 +62,18 @@ def test_arena_sizing_of_the_benchmark_configs(name):
     assert P.dds_arena_bytes(P.Spec.from_workload(half), wl.K, wl.W) < n
 
 
+def test_paper_experiment_workloads_are_resnet20():
+    from dds_inputs.configs import PAPER_WORKLOAD_NAMES
+    assert set(PAPER_WORKLOAD_NAMES) == {"paper_r20_S1K1", "paper_r20_S1K2", "paper_r20_S4K1", "paper_r20_S4K2"}
+    for name in PAPER_WORKLOAD_NAMES:
+        wl = workload(name)
+        convs = [o for o in wl.ops if o["op"] == "conv"]
+        shortcuts = [o for o in wl.ops if o["op"] == "res_add" and o["shortcut"]]
+        assert len(convs) + 1 == 20 and len(shortcuts) == 2  # 19 convs + 1 linear; two projection blocks
+        assert wl.B == 194 and wl.K == len(wl.bounds) - 1 and wl.W in (1, 4)
+        assert P.dds_arena_bytes(P.Spec.from_workload(wl), wl.K, wl.W) > 0
+
+
 def _spec(ops, bounds, in_shape=(3, 8, 8), precision="f32"):
     return P.Spec(ops, bounds, in_shape, 10, 4, precision, 0.1, 0.0)
 
