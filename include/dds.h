@@ -147,10 +147,12 @@ double dds_gemm_flops_per_step(const dds_ctx* ctx);
  * launch's duration includes the time it shares the chip with other modules' kernels;
  * enable = 2: modules run one after another on the caller's stream, so every launch has
  * the chip to itself; 0: off. Enabling also clears the totals.
- * dds_profile_read fills 9 doubles: for class 0 forward, 1 dgrad, 2 wgrad:
- * summed milliseconds, number of launches, summed algorithmic FLOPs (2*M*N*K). */
+ * dds_profile_read fills 18 doubles: for each of six classes summed milliseconds, number of
+ * launches, summed algorithmic FLOPs (2*M*N*K). Classes 0 forward, 1 dgrad, 2 wgrad launches
+ * taken by the generic implicit-GEMM kernels; 3, 4, 5 the same three kinds taken by the
+ * asynchronous global->LDS kernels (3x3 stride-1 forward / dgrad; 3x3 and stride-2 wgrad). */
 int dds_profile(dds_ctx* ctx, int enable);
-int dds_profile_read(const dds_ctx* ctx, double* out9);
+int dds_profile_read(const dds_ctx* ctx, double* out18);
 
 const char* dds_last_error(void);
 

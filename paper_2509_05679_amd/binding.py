@@ -200,11 +200,12 @@ class Trainer:
         _check(lib.dds_profile(self.ctx, int(enable)))
 
     def dds_profile_read(self):
-        """{class: (ms, launches, flops)} for forward / dgrad / wgrad launches."""
-        out = (C.c_double * 9)()
+        """{class: (ms, launches, flops)}; classes forward / dgrad / wgrad on the generic kernels and
+        forward_dma / dgrad_dma / wgrad_dma on the asynchronous global->LDS kernels."""
+        out = (C.c_double * 18)()
         _check(lib.dds_profile_read(self.ctx, out))
-        return {name: (out[3 * i], int(out[3 * i + 1]), out[3 * i + 2])
-                for i, name in enumerate(("forward", "dgrad", "wgrad"))}
+        names = ("forward", "dgrad", "wgrad", "forward_dma", "dgrad_dma", "wgrad_dma")
+        return {name: (out[3 * i], int(out[3 * i + 1]), out[3 * i + 2]) for i, name in enumerate(names)}
 
     def close(self):
         if getattr(self, "ctx", None):

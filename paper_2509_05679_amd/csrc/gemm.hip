@@ -1529,14 +1529,14 @@ inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 #define HALO_BKB 64
 #endif
 template <typename T>
-void launch_conv_t(const ConvParams& p, hipStream_t s) {
+int launch_conv_t(const ConvParams& p, hipStream_t s) {
   constexpr int BKB = 64;
-  if (launch_dma<T>(p, s)) return;
+  if (launch_dma<T>(p, s)) return 1;
   HaloGeom g;
   if (halo_geometry<T>(p, g)) {
     if (p.ldy <= 64) launch_halo_inst<T, 64, 64, 64, HALO_BKB>(p, g, s);
     else launch_halo_inst<T, 128, 128, 64, HALO_BKB>(p, g, s);
-    return;
+    return 0;
   }
   // dgrad of a stride-2 convolution: workgroups per parity class (class (0,0) is the largest)
   const bool s2 = p.dgrad && p.stride == 2 && p.Cx % (BKB / (int)sizeof(T)) == 0 &&
@@ -1555,6 +1555,7 @@ void launch_conv_t(const ConvParams& p, hipStream_t s) {
     else if (p.dgrad) conv_gemm_kernel<T, 128, 128, 64, 64, BKB, true><<<grid, 256, 0, s>>>(p, 0);
     else conv_gemm_kernel<T, 128, 128, 64, 64, BKB, false><<<grid, 256, 0, s>>>(p, 0);
   }
+  return 0;
 }
 
 template <int TWLOG, int THLOG, bool S2>
@@ -1629,9 +1630,9 @@ bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
 }
 
 template <typename T>
-void launch_wgrad_t(const WgradParams& p, hipStream_t s) {
+int launch_wgrad_t(const WgradParams& p, hipStream_t s) {
   constexpr int CE = 16 / sizeof(T);
-  if (sizeof(T) == 2 && launch_wgrad_dma(p, s)) return;
+  if (sizeof(T) == 2 && launch_wgrad_dma(p, s)) return 1;
   if (p.Mout <= 64 && p.NK + CE <= 128) {  // e.g. the stem: 3 input channels, 9 taps
     dim3 grid(cdiv(p.Mout, 64), 1, p.nsplit);
     wgrad_gemm_kernel<T, 64, 128, 32, 64><<<grid, 256, 0, s>>>(p);
@@ -1642,18 +1643,17 @@ void launch_wgrad_t(const WgradParams& p, hipStream_t s) {
     dim3 grid(cdiv(p.Mout, 128), cdiv(p.NK + CE, 128), p.nsplit);
     wgrad_gemm_kernel<T, 128, 128, 64, 64><<<grid, 256, 0, s>>>(p);
   }
+  return 0;
 }
 
 }  // namespace
 
-void launch_conv(int dt, const ConvParams& p, hipStream_t s) {
-  if (dt == DT_F32) launch_conv_t<float>(p, s);
-  else launch_conv_t<bf16_t>(p, s);
+int launch_conv(int dt, const ConvParams& p, hipStream_t s) {
+  return dt == DT_F32 ? launch_conv_t<float>(p, s) : launch_conv_t<bf16_t>(p, s);
 }
 
-void launch_wgrad(int dt, const WgradParams& p, hipStream_t s) {
-  if (dt == DT_F32) launch_wgrad_t<float>(p, s);
-  else launch_wgrad_t<bf16_t>(p, s);
+int launch_wgrad(int dt, const WgradParams& p, hipStream_t s) {
+  return dt == DT_F32 ? launch_wgrad_t<float>(p, s) : launch_wgrad_t<bf16_t>(p, s);
 }
 
 int wgrad_choose_split(int dt, const WgradParams& shape, int W) {

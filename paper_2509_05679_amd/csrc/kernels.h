@@ -98,8 +98,10 @@ struct UpdateDesc {
   int Cout, RS, Cinpad, Cin, Coutpad;
 };
 
-void launch_conv(int dt, const ConvParams& p, hipStream_t s);
-void launch_wgrad(int dt, const WgradParams& p, hipStream_t s);
+// Both return the kernel family that took the launch: 0 = generic implicit GEMM (register-staged),
+// 1 = the asynchronous global->LDS kernels (conv3x3_dma_kernel / wgrad_dma_kernel).
+int launch_conv(int dt, const ConvParams& p, hipStream_t s);
+int launch_wgrad(int dt, const WgradParams& p, hipStream_t s);
 // Chooses the split count of the pixel reduction for a wgrad problem: a multiple of the replica
 // count W, so that no split mixes two replicas. shape: every field that describes the layer
 // (Nimg, H, W, Cx, Ho, Wo, Mout, ldy, R, S, stride, pad, NK, P, zeros non-null); nsplit,
