@@ -717,18 +717,19 @@ struct DmaGeom {
 };
 
 template <typename T, int BM, int BN, int WM, int WN, int PS, int KB>
-__global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGeom dg) {
+__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) == 4 ? 2 : 1) void conv3x3_dma_kernel(ConvParams p, DmaGeom dg) {
   constexpr int ES = sizeof(T);
+  constexpr int NW = (BM / WM) * (BN / WN);  // waves per workgroup (each owns a WM x WN sub-tile)
   constexpr int FROWS = 1024 / KB;     // LDS rows per wave fill (KB = bytes of channels per row: 64 or 128)
   constexpr int CPR = KB / 16;         // 16-byte columns per row
-  constexpr int WL = BN / FROWS / 4;   // weight fills per lane per stage
+  constexpr int WL = BN / FROWS / NW;   // weight fills per lane per stage
   constexpr int NKS = KB / 32;         // MFMA k-steps per stage
   constexpr int FB = KB == 128 ? 3 : 2;   // swizzle bits = log2(CPR)
   constexpr int RPL = KB == 128 ? 1 : 2;  // log2(rows per 256 bytes of LDS)
   static_assert(KB == 64 || KB == 128, "row depth");
   static_assert(WL >= 1, "weight tile smaller than one fill per wave");
   constexpr int NI = WM / 32, NJ = WN / 32;
-  static_assert((BM / WM) * (BN / WN) == 4, "four waves");
+  static_assert(NW == 4 || NW == 8, "four or eight waves");
   extern __shared__ __align__(16) char smem[];
   const HaloGeom& g = dg.h;
   const int prow = dg.patch_rows;
@@ -760,7 +761,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   auto patch_swizzle = [&](int xx, int yy) { return ((xx >> RPL) & sw_mx) | ((yy & sw_my) << sw_nx); };
 
   // pixel-offset table of the patch rows: pixel index in the gathered tensor, or -1 (zero row)
-  for (int row = tid; row < prow; row += 256) {
+  for (int row = tid; row < prow; row += 64 * NW) {
     int v = -1;
     if (row < g.patch_pix) {
       const int im = row / g.PP, rem = row - im * g.PP;
@@ -790,12 +791,12 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     int offs[NPRO];
 #pragma unroll
     for (int j = 0; j < NPRO; ++j) {
-      const int wl = wave + 4 * j;
+      const int wl = wave + NW * j;
       offs[j] = tab[(wl < pw_total ? wl * FROWS : 0) + l8];  // pixel * CPR + f, or -1
     }
 #pragma unroll
     for (int j = 0; j < NPRO; ++j) {
-      const bool ok = wave + 4 * j < pw_total && offs[j] >= 0;
+      const bool ok = wave + NW * j < pw_total && offs[j] >= 0;
       const int o = ok ? offs[j] : 0;
       const char* a = (const char*)p.x + (size_t)(o >> FB) * pixbytes + ((pcol ^ (o & (CPR - 1))) << 4);
       pro_src[j] = ok ? a : zsrc;
@@ -803,7 +804,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   }
   auto patch_src = [&](int j) -> const char* { return pro_src[j]; };
   auto patch_dst = [&](int j, int buf) {
-    const int wl = wave + 4 * j;
+    const int wl = wave + NW * j;
     return wl < pw_total ? lds_pbuf + buf * pbuf_bytes + wl * 1024 : lds_dump;
   };
   constexpr int NPF = 7 * PS;  // patch fills per wave and chunk issued inside the loop
@@ -815,14 +816,14 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   uint32_t wvo[WL];
 #pragma unroll
   for (int u = 0; u < WL; ++u) {
-    const int gn = n0 + (wave + 4 * u) * FROWS + l8;
+    const int gn = n0 + (wave + NW * u) * FROWS + l8;
     const int c16 = (pcol ^ swz(l8 + (wave & 1) * FROWS)) * 16;
     wvo[u] = (uint32_t)(gn < p.Nout ? gn : p.Nout - 1) * (uint32_t)(9 * pixbytes) + c16;
   }
   auto fill_w = [&](int chunk, int tap, int slot) {
     const char* base = (const char*)p.w + (size_t)tap * pixbytes + (size_t)chunk * KB;  // wave-uniform
 #pragma unroll
-    for (int u = 0; u < WL; ++u) dma16s(base, wvo[u], lds_wring + slot * (BN * KB) + (wave + 4 * u) * 1024);
+    for (int u = 0; u < WL; ++u) dma16s(base, wvo[u], lds_wring + slot * (BN * KB) + (wave + NW * u) * 1024);
   };
 
   // pixel of the 32-pixel fragment held by this lane: quads {0,3,5,6} -> pixels 0..15, {1,2,4,7} -> 16..31
@@ -847,7 +848,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   // the set-up (fragment addresses, sign words, accumulators) so that it runs under the copies' latency.
 #pragma unroll
   for (int j = 0; j < NPRO; ++j)
-    if (wave + 4 * j < pw_total) dma16(pro_src[j], patch_dst(j, 0));
+    if (wave + NW * j < pw_total) dma16(pro_src[j], patch_dst(j, 0));
   fill_w(0, 0, 0);
   fill_w(0, 1, 1);
 
@@ -941,7 +942,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
   constexpr int ROWB = BN * ES;        // bytes per tile row
   constexpr int NCOL = ROWB / 16;      // 16-byte columns per row
   constexpr int RPF = 64 / NCOL;       // rows per wave fill
-  constexpr int FPW = BM / RPF / 4;    // fills per wave
+  constexpr int FPW = BM / RPF / NW;    // fills per wave
   int res_off = -1, mask_off = -1, nregions = 0;
   const int ab_off = (int)(lds_dump - lds0);  // the dump block now holds alpha * bias of this tile's channels
   float* ab_lds = (float*)(smem + ab_off);
@@ -957,7 +958,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
       const int rbase = region * BM * ROWB;
 #pragma unroll
       for (int u = 0; u < FPW; ++u) {
-        const int f = wave + 4 * u;
+        const int f = wave + NW * u;
         const int row = f * RPF + lane / NCOL, slot = lane % NCOL;
         const int gc = (slot ^ row) & (NCOL - 1);
         const int x = row & TWm, y = (row >> g.tw_log) & THm, im = row >> (g.tw_log + g.th_log);
@@ -997,7 +998,7 @@ __global__ __launch_bounds__(256, 2) void conv3x3_dma_kernel(ConvParams p, DmaGe
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < FPW; ++u) {
-      const int f = wave + 4 * u;
+      const int f = wave + NW * u;
       const int row = f * RPF + lane / NCOL, slot = lane % NCOL;
       const int gc = (slot ^ row) & (NCOL - 1);
       const int x = row & TWm, y = (row >> g.tw_log) & THm, im = row >> (g.tw_log + g.th_log);
@@ -1053,11 +1054,12 @@ bool halo_geometry(const ConvParams& p, HaloGeom& g, int BM = 256, int chunk_byt
 template <typename T, int BM, int BN, int WM, int WN, int PS, int KB>
 bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
   constexpr int FROWS = 1024 / KB;
+  constexpr int NW = (BM / WM) * (BN / WN);
   DmaGeom dg;
   dg.h = h;
   dg.patch_rows = (h.patch_pix + FROWS - 1) / FROWS * FROWS;
   dg.tab_bytes = (dg.patch_rows * 4 + 1023) / 1024 * 1024;
-  const int fills_per_wave = (dg.patch_rows / FROWS + 3) / 4;
+  const int fills_per_wave = (dg.patch_rows / FROWS + NW - 1) / NW;
   if (p.Cx * (int)sizeof(T) % KB != 0) return false;
   const int nchunks = p.Cx * (int)sizeof(T) / KB;
   if (fills_per_wave > 7) return false;  // the kernel keeps seven prologue sources per lane
@@ -1076,7 +1078,7 @@ bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
   }
   const int groups = (p.Nimg + h.imgs - 1) / h.imgs;
   dim3 grid(groups * h.tiles_w * h.tiles_h, (p.ldy + BN - 1) / BN);
-  conv3x3_dma_kernel<T, BM, BN, WM, WN, PS, KB><<<grid, 256, smem, s>>>(p, dg);
+  conv3x3_dma_kernel<T, BM, BN, WM, WN, PS, KB><<<grid, 64 * NW, smem, s>>>(p, dg);
   return true;
 }
 
