@@ -517,13 +517,9 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int til
   }
 }
 
-// ------------------------------------------------------------------ 3x3 stride-1 forward / dgrad with an LDS halo patch
-// The workgroup owns 256 output pixels (a TH x TW rectangle of one image, or IMGS whole
-// small images) and BN output channels. Per 128-byte channel chunk the input patch
-// including its one-pixel halo is staged in LDS ONCE and all nine taps read their A
-// operands from it at shifted addresses, so activations cross the L2 about 1.3x instead
-// of 9x; zero padding is materialised in the patch, not tested in the inner loop. The
-// weight tile of each (tap, chunk) streams through a double buffer.
+// ------------------------------------------------------------------ tile geometry of the 3x3 stride-1 kernels
+// A workgroup owns a TH x TW rectangle of one image (or IMGS whole small images) and stages the
+// input patch of that rectangle including its one-pixel halo in LDS.
 struct HaloGeom {
   int tw_log, th_log;      // log2 of the tile width / height in pixels
   int tiles_w, tiles_h;    // tiles per image
@@ -534,155 +530,11 @@ struct HaloGeom {
   int flip;                // dgrad: tap (r,s) reads the patch at (2-r, 2-s)
 };
 
-template <typename T, int BN, int WM, int WN, int BKB>
-__global__ __launch_bounds__(256, 2) void conv3x3_halo_kernel(ConvParams p, HaloGeom g) {
-  constexpr int ES = sizeof(T);
-  constexpr int BM = 256, LDK = BKB + 16;
-  constexpr int CPR = BKB / 16;          // 16-byte columns per LDS row
-  constexpr int WP = BN * CPR / 256;     // 16-byte weight chunks per thread per (tap, chunk)
-  constexpr int PSTEP = 256 / CPR;       // patch pixels covered by one pass of all threads
-  static_assert((BM / WM) * (BN / WN) == 4, "four waves");
-  extern __shared__ __align__(16) char smem[];
-  char* patch = smem;
-  char* wbuf = smem + g.patch_bytes;
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wave_m = wave % (BM / WM), wave_n = wave / (BM / WM);
-  const int tiles_per_img = g.tiles_w * g.tiles_h;
-  const int grp = blockIdx.x / tiles_per_img, tin = blockIdx.x - grp * tiles_per_img;
-  const int th_idx = tin / g.tiles_w, tw_idx = tin - th_idx * g.tiles_w;
-  const int img0 = grp * g.imgs, h0 = th_idx << g.th_log, w0 = tw_idx << g.tw_log;
-  const int n0 = blockIdx.y * BN;
-  const int TWm = (1 << g.tw_log) - 1, THm = (1 << g.th_log) - 1;
-  const int PH = (1 << g.th_log) + 2;
-
-  int abase[WM / 32], bbase[WN / 32];
-#pragma unroll
-  for (int i = 0; i < WM / 32; ++i) {
-    const int m = wave_m * WM + i * 32 + (lane & 31);
-    const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
-    abase[i] = (im * g.PP + y * g.PW + x) * LDK + (lane >> 5) * 16;
-  }
-#pragma unroll
-  for (int j = 0; j < WN / 32; ++j) bbase[j] = (wave_n * WN + j * 32 + (lane & 31)) * LDK + (lane >> 5) * 16;
-
-  // weight stream: iteration it = chunk*9 + tap
-  const int nchunks = (p.Cx * ES) / BKB;
-  const int niter = nchunks * 9;
-  const char* wrow[WP];
-  bool wok[WP];
-#pragma unroll
-  for (int q = 0; q < WP; ++q) {
-    const int id = tid + q * 256, row = id / CPR, c16 = id % CPR;
-    wok[q] = n0 + row < p.Nout;
-    wrow[q] = (const char*)p.w + (size_t)(wok[q] ? n0 + row : 0) * 9 * p.Cx * ES + c16 * 16;
-  }
-  uint4 wregA[WP], wregB[WP];  // two named register sets (no dynamic indexing: stays in VGPRs)
-  // Loads are unconditional (rows past the end are clamped to row 0 and zeroed when parked
-  // in LDS): with no branch around a load the compiler can count the requests in flight and
-  // wait for exactly the older ones, which is what lets a request span two compute phases.
-  auto load_w = [&](int it, uint4 (&dst)[WP]) {
-    const int chunk = it / 9, tap = it - chunk * 9;
-    const size_t off = (size_t)tap * p.Cx * ES + (size_t)chunk * BKB;
-#pragma unroll
-    for (int q = 0; q < WP; ++q) dst[q] = *(const uint4*)(wrow[q] + off);
-  };
-  auto store_w = [&](int slot, const uint4 (&src)[WP]) {
-    char* wb = wbuf + slot * BN * LDK;
-#pragma unroll
-    for (int q = 0; q < WP; ++q) {
-      const int id = tid + q * 256;
-      *(uint4*)(wb + (id / CPR) * LDK + (id % CPR) * 16) = keep_if(wok[q], src[q]);
-    }
-  };
-  // patch loader: this thread owns 16-byte column c16 = tid%CPR of patch pixels tid/CPR + PSTEP*k
-  auto load_patch = [&](int chunk) {
-    const int c16 = tid % CPR;
-    int pp = tid / CPR;
-    int im = pp / g.PP, rem = pp - im * g.PP;
-    int yy = rem / g.PW, xx = rem - yy * g.PW;
-    const char* src = (const char*)p.x + (size_t)chunk * BKB + c16 * 16;
-    for (; pp < g.patch_pix; pp += 4 * PSTEP) {
-      uint4 v[4];
-      int pq[4];
-      bool ok[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        pq[u] = pp + u * PSTEP;
-        const int gi = img0 + im, gh = h0 + yy - 1, gw = w0 + xx - 1;
-        ok[u] = pq[u] < g.patch_pix && gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W;
-        const size_t o = ok[u] ? ((((size_t)gi * p.H + gh) * p.W + gw) * p.Cx) * ES : 0;
-        v[u] = *(const uint4*)(src + o);
-        xx += PSTEP;
-        while (xx >= g.PW) { xx -= g.PW; ++yy; }
-        while (yy >= PH) { yy -= PH; ++im; }
-      }
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        if (pq[u] < g.patch_pix) *(uint4*)(patch + pq[u] * LDK + c16 * 16) = keep_if(ok[u], v[u]);
-    }
-  };
-
-  f32x16_t acc[WN / 32][WM / 32];
-#pragma unroll
-  for (int j = 0; j < WN / 32; ++j)
-#pragma unroll
-    for (int i = 0; i < WM / 32; ++i)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[j][i][e] = 0.f;
-
-  // One pipeline stage. Weight tile it+2 is requested before the MFMAs of tile it and tile
-  // it+1 (requested a whole stage earlier, in `nxt`) is parked in LDS after them, so a
-  // request has two compute phases to land. Two LDS slots: it+1 goes where it-1 was.
-  auto stage = [&](int it, uint4 (&nxt)[WP], uint4 (&fre)[WP]) {
-    const int chunk = it / 9, tap = it - chunk * 9;
-    if (tap == 0) {
-      load_patch(chunk);  // the barrier that ended the previous stage freed the patch
-      __syncthreads();
-    }
-    if (it + 2 < niter) load_w(it + 2, fre);
-    const int r = tap / 3, sx = tap - r * 3;
-    const int tapoff = ((g.flip ? 2 - r : r) * g.PW + (g.flip ? 2 - sx : sx)) * LDK;
-    const char* wb = wbuf + (it & 1) * BN * LDK;
-#pragma unroll
-    for (int ks = 0; ks < BKB / 32; ++ks) {
-      uint4 a[WM / 32], b[WN / 32];
-#pragma unroll
-      for (int i = 0; i < WM / 32; ++i) a[i] = *(const uint4*)(patch + abase[i] + tapoff + ks * 32);
-#pragma unroll
-      for (int j = 0; j < WN / 32; ++j) b[j] = *(const uint4*)(wb + bbase[j] + ks * 32);
-#pragma unroll
-      for (int j = 0; j < WN / 32; ++j)
-#pragma unroll
-        for (int i = 0; i < WM / 32; ++i) mfma16B<T>(b[j], a[i], acc[j][i]);
-    }
-    if (it + 1 < niter) store_w((it + 1) & 1, nxt);
-    __syncthreads();  // tile it+1 visible; tile it and (at a chunk end) the patch are free
-  };
-
-  load_w(0, wregA);
-  store_w(0, wregA);  // made visible by the barrier after the first patch load
-  if (niter > 1) load_w(1, wregB);
-  for (int it = 0; it < niter; it += 2) {
-    stage(it, wregB, wregA);
-    if (it + 1 < niter) stage(it + 1, wregA, wregB);
-  }
-
-  const int nb = n0 + wave_n * WN + 4 * (lane >> 5);
-  float bias[WN / 32][4][4];
-  load_bias_groups<WN / 32>(p, nb, bias);
-#pragma unroll
-  for (int i = 0; i < WM / 32; ++i) {
-    const int m = wave_m * WM + i * 32 + (lane & 31);
-    const int x = m & TWm, y = (m >> g.tw_log) & THm, im = m >> (g.tw_log + g.th_log);
-    const int gi = img0 + im;
-    const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
-    epilogue_tile<T, WN / 32, WM / 32>(p, acc, i, gi < p.Nimg, pix, nb, bias);
-  }
-}
-
 // ------------------------------------------------------------------ 3x3 stride-1 forward / dgrad, asynchronous LDS fills
-// Same tiling as the halo kernel above, but every operand byte travels global -> LDS
+// The workgroup owns BM output pixels and BN output channels. Per 64-byte channel chunk the
+// input patch with its halo is staged in LDS ONCE and all nine taps read their MFMA operands
+// from it at shifted rows, so activations cross the L2 about 1.3x instead of 9x; zero padding
+// is materialised in the patch, not tested in the inner loop. Every operand byte travels global -> LDS
 // with global_load_lds_dwordx4 (no staging registers, lane L of a wave fills bytes
 // [16L, 16L+16) of a 1 KiB LDS block), issued two pipeline stages (tap, channel chunk)
 // ahead of its use: weight tiles rotate through three LDS slots and the next channel
@@ -1021,7 +873,7 @@ inline int ilog2_exact(int v) {
   return (1 << l) == v ? l : -1;
 }
 
-// Fills g and returns true when the halo kernel covers this problem.
+// Fills g and returns true when the 3x3 stride-1 tiling covers this problem.
 template <typename T>
 bool halo_geometry(const ConvParams& p, HaloGeom& g, int BM = 256, int chunk_bytes = 64) {
   const int CK = chunk_bytes / (int)sizeof(T);
@@ -1106,20 +958,6 @@ bool launch_dma(const ConvParams& p, hipStream_t s) {
   }
   if (halo_geometry<T>(p, h, 128, KB) && launch_dma_inst<T, 128, 128, 64, 64, 1, KB>(p, h, s)) return true;
   return false;
-}
-
-template <typename T, int BN, int WM, int WN, int BKB>
-void launch_halo_inst(const ConvParams& p, HaloGeom g, hipStream_t s) {
-  static bool attr_set = false;
-  g.patch_bytes = (g.patch_pix * (BKB + 16) + 255) / 256 * 256;
-  const int smem = g.patch_bytes + 2 * BN * (BKB + 16);
-  if (!attr_set) {
-    (void)hipFuncSetAttribute((const void*)conv3x3_halo_kernel<T, BN, WM, WN, BKB>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    attr_set = true;
-  }
-  const int groups = (p.Nimg + g.imgs - 1) / g.imgs;
-  dim3 grid(groups * g.tiles_w * g.tiles_h, (p.ldy + BN - 1) / BN);
-  conv3x3_halo_kernel<T, BN, WM, WN, BKB><<<grid, 256, smem, s>>>(p, g);
 }
 
 // ------------------------------------------------------------------ wgrad
@@ -1527,19 +1365,10 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
-#ifndef HALO_BKB
-#define HALO_BKB 64
-#endif
 template <typename T>
 int launch_conv_t(const ConvParams& p, hipStream_t s) {
   constexpr int BKB = 64;
   if (launch_dma<T>(p, s)) return 1;
-  HaloGeom g;
-  if (halo_geometry<T>(p, g)) {
-    if (p.ldy <= 64) launch_halo_inst<T, 64, 64, 64, HALO_BKB>(p, g, s);
-    else launch_halo_inst<T, 128, 128, 64, HALO_BKB>(p, g, s);
-    return 0;
-  }
   // dgrad of a stride-2 convolution: workgroups per parity class (class (0,0) is the largest)
   const bool s2 = p.dgrad && p.stride == 2 && p.Cx % (BKB / (int)sizeof(T)) == 0 &&
                   (p.x2 == nullptr || p.Cx2 % (BKB / (int)sizeof(T)) == 0);
