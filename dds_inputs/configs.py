@@ -216,6 +216,22 @@ def tiny_resnet(K=2, W=2, B=4, hw=8, c=8, precision="f32", steps=8) -> Workload:
                     momentum=0.0, steps=steps, extra={"blocks": 3, "res_scale": scale})
 
 
+def odd_resnet(precision="f32", K=2, W=2, B=3, h=7, w=9, c=16, steps=8) -> Workload:
+    """Awkward shapes on purpose: odd image sides (so a stride-2 block halves 7 x 9 to 4 x 5), an odd
+    per-replica batch, a projection block whose channel counts still reach the stride-2 dgrad path
+    that folds the shortcut in, and a 10-channel 1x1 conv whose channel stride is padded."""
+    scale = 1.0 / math.sqrt(2)
+    ops = [_conv(3, c), _relu()]
+    ops += _block(c, 2 * c, 2, scale)
+    cut = len(ops)
+    ops += _block(2 * c, 2 * c, 1, scale)
+    ops += [_conv(2 * c, 10, 1, 1), _relu(), {"op": "gap"}, _linear(10, 10), {"op": "softmax_ce"}]
+    bounds = [0, len(ops)] if K == 1 else [0, cut, len(ops)]
+    return Workload(name=f"odd_resnet_K{K}", ops=ops, bounds=bounds, K=K, W=W, B=B,
+                    in_shape=(3, h, w), classes=10, precision=precision, lr=0.05,
+                    momentum=0.0, steps=steps, extra={"blocks": 2, "res_scale": scale})
+
+
 def tiny_cnn(K=2, W=2, B=4, hw=8, c=4, precision="f32", steps=8, momentum=0.9) -> Workload:
     """conv-relu-maxpool x2, gap, linear: the cfg1 structure at toy size."""
     ops = [_conv(3, c), _relu(), {"op": "maxpool2"}]

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 from dds_inputs import workload
-from dds_inputs.configs import tiny_cnn, tiny_mlp, tiny_resnet
+from dds_inputs.configs import odd_resnet, tiny_cnn, tiny_mlp, tiny_resnet
 from parity import flat_init, rel_errors, run_hip, run_oracle
 
 pytestmark = pytest.mark.gpu
@@ -115,6 +115,45 @@ def test_cfg3_resnet56_reduced_batch_bf16():
     # depths up to 15; per-replica batch 2 keeps the oracle leg short
     wl = workload("cfg3_resnet56", B=2)
     _compare(wl, seed=0, T=2 * (wl.K - 1) + 6)
+
+
+def test_odd_shapes_fp32_and_bf16():
+    # 7 x 9 images, batch 3, stride-2 projection block (parity classes of unequal size, shortcut
+    # folded into the dgrad), a conv with 10 output channels (padded channel stride)
+    _compare(odd_resnet("f32"), seed=5, T=8, every_step=True, update_tol=UPDATE_TOL_TINY_F32)
+    _compare(odd_resnet("bf16", c=32), seed=6, T=8)
+    _compare(odd_resnet("f32", K=1, W=1, B=1), seed=7, T=4, every_step=True, update_tol=UPDATE_TOL_TINY_F32)
+
+
+def test_repeatable_and_independent_of_stream_layout():
+    """The same inputs give bit-identical parameters on a second run (fixed-order reductions, no
+    atomics), and also when the modules are serialised on the caller's stream while profiling."""
+    import numpy as np
+    import torch
+    import paper_2509_05679_amd as P
+    from dds_inputs import make_batch, make_params
+    wl = workload("cfg2_resnet18", B=4)
+
+    def run(profile_mode):
+        tr = P.Trainer(P.Spec.from_workload(wl), wl.W)
+        init = make_params(wl, 0)
+        for k0 in range(wl.K):
+            tr.dds_set_params(k0, init[k0])
+        if profile_mode:
+            tr.dds_profile(profile_mode)
+        for t in range(2 * (wl.K - 1) + 4):
+            xs = [torch.from_numpy(make_batch(wl, 0, t, s)[0]).cuda() for s in range(wl.W)]
+            ys = [torch.from_numpy(make_batch(wl, 0, t, s)[1]).cuda() for s in range(wl.W)]
+            tr.dds_step(xs, ys)
+        torch.cuda.synchronize()
+        out = [tr.dds_get_params(k0) for k0 in range(wl.K)]
+        tr.close()
+        return out
+
+    a, b, c = run(0), run(0), run(2)
+    for k0 in range(wl.K):
+        assert np.array_equal(a[k0], b[k0]), f"module {k0}: two identical runs differ"
+        assert np.array_equal(a[k0], c[k0]), f"module {k0}: serialised run differs from the concurrent one"
 
 
 def test_paper_resnet20_shapes_reduced_batch_bf16():
