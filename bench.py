@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--workload", default="cfg2_resnet18")
     ap.add_argument("--batch", type=int, default=None, help="override per-replica batch (debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--mixing", default="mean",
+                    help="'mean' (the headline path: exact averaging, one weight copy) or 'ring:ALPHA' "
+                         "(ring communication graph, every data-group keeps its own weights)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (all K x W module-replica pairs live on it); "
@@ -98,7 +101,14 @@ def main():
     wl = workload(args.workload, B=args.batch)
     warmup = args.warmup if args.warmup is not None else 2 * (wl.K - 1) + 5
     warmup = max(warmup, 2 * (wl.K - 1))  # timed steps are steady state: every module forwards, backwards, updates
-    spec = P.Spec.from_workload(wl)
+    mixing = None
+    if args.mixing != "mean":
+        from dds_inputs.configs import ring_mixing
+        kind, _, alpha = args.mixing.partition(":")
+        if kind != "ring" or not alpha:
+            sys.exit("bench.py: --mixing takes 'mean' or 'ring:ALPHA'")
+        mixing = ring_mixing(wl.W, float(alpha))
+    spec = P.Spec.from_workload(wl, mixing)
     tr = P.Trainer(spec, wl.W)
     init = make_params(wl, 0)
     for k0 in range(wl.K):
@@ -191,7 +201,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: K={wl.K} modules, W={wl.W} replicas x batch {wl.B}, {wl.precision}",
                    "launches_per_step": launches, "wall_ms_per_step": wall * 1e3 / args.steps,
-                   "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30},
+                   "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30, "mixing": args.mixing,
+                   "consensus_error": tr.dds_consensus_error() if mixing is not None else 0.0},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": traffic,
                      "kernel": dom_name,

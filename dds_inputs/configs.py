@@ -257,3 +257,22 @@ def tiny_mlp(K=3, W=2, B=4, feat=12, hidden=8, precision="f32", steps=10) -> Wor
     return Workload(name=f"tiny_mlp_K{K}", ops=ops, bounds=bounds, K=K, W=W, B=B,
                     in_shape=(feat, 1, 1), classes=10, precision=precision, lr=0.05,
                     momentum=0.0, steps=steps)
+
+
+# ----------------------------------------------------------------------------- communication graphs
+def ring_mixing(W: int, alpha: float):
+    """Mixing matrix of a ring of W data-groups (Section 2.3): alpha towards each of the two
+    neighbours, the rest on the diagonal. W = 2 is a single edge. Returned as nested lists."""
+    P = [[0.0] * W for _ in range(W)]
+    edges = {(i, (i + 1) % W) for i in range(W)} if W > 2 else ({(0, 1)} if W == 2 else set())
+    for i, j in edges:
+        P[i][j] += alpha
+        P[j][i] += alpha
+    for i in range(W):
+        P[i][i] = 1.0 - sum(P[i][j] for j in range(W) if j != i)
+    return P
+
+
+def complete_mixing(W: int):
+    """Complete graph with weight 1/W everywhere: the exact mean."""
+    return [[1.0 / W] * W for _ in range(W)]

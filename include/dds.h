@@ -72,6 +72,12 @@ typedef struct dds_spec {
   int32_t precision;       /* DDS_F32 | DDS_BF16_F32MASTER */
   float lr;                /* default step size (see dds_step) */
   float momentum;          /* 0 = plain SGD; else v <- mu v + g, w <- w - lr v */
+  const float* mixing;     /* host; NULL: every data-group mixes with every other with weight 1/W
+                              (exact mean, one weight copy per module -- the hot path). Else the
+                              W x W row-major matrix P of Section 2.3 (symmetric, rows summing to
+                              1, entries in [0,1]); each data-group then keeps its own weights and
+                              Section 3.3's update u_s = w_s - lr g_s, w_s <- sum_r P[s][r] u_r runs
+                              as written. Read during dds_arena_bytes / dds_create only. */
 } dds_spec;
 
 typedef struct dds_ctx dds_ctx;
@@ -116,6 +122,19 @@ int64_t dds_param_count(const dds_ctx* ctx, int module);
  * (Algorithm 1 input: the initial weights, identical in every data-group). */
 int dds_get_params(dds_ctx* ctx, int module, float* dst_device, size_t n_floats, void* hip_stream);
 int dds_set_params(dds_ctx* ctx, int module, const float* src_device, size_t n_floats, void* hip_stream);
+
+/* dds_get_params for the weights of one data-group (Section 3.3: agent (s,k) holds its own
+ * w_{s,k}). replica in [0,W). Without a mixing matrix every data-group holds the same
+ * weights and this equals dds_get_params; with one, dds_get_params returns data-group 0's
+ * and dds_set_params gives all of them the same initial weights. */
+int dds_get_params_replica(dds_ctx* ctx, int module, int replica, float* dst_device, size_t n_floats,
+                           void* hip_stream);
+
+/* Disagreement between the data-groups' weights as the experiment section measures it:
+ * delta = max over parameter tensors l (each weight and each bias of every module) and
+ * data-groups s of || w_{s,l} - (1/W) sum_r w_{r,l} ||_2, accumulated in fp64 from the fp32
+ * master weights. Exactly 0 without a mixing matrix. Synchronises stream. */
+int dds_consensus_error(dds_ctx* ctx, double* host_out, void* hip_stream);
 
 /* One iteration t of every module (Algorithm 1 loop body for all S*K agents).
  * x_device[s]: replica s's mini-batch, fp32 [B,in_c,in_h,in_w] (NCHW);

@@ -24,7 +24,7 @@ OPS = {"conv": 1, "linear": 2, "relu": 3, "maxpool2": 4, "gap": 5, "res_begin": 
 PRECISION = {"f32": 0, "bf16": 1}
 
 EXPORTS = ["dds_schedule", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
-           "dds_get_params", "dds_set_params", "dds_step", "dds_get_loss", "dds_step_count",
+           "dds_get_params", "dds_set_params", "dds_get_params_replica", "dds_consensus_error", "dds_step", "dds_get_loss", "dds_step_count",
            "dds_launches_last_step", "dds_gemm_flops_per_step", "dds_profile", "dds_profile_read",
            "dds_last_error"]
 
@@ -39,7 +39,8 @@ class dds_spec(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layers", C.POINTER(dds_layer)),
                 ("bounds", C.POINTER(C.c_int32)), ("in_c", C.c_int32), ("in_h", C.c_int32),
                 ("in_w", C.c_int32), ("classes", C.c_int32), ("batch", C.c_int32),
-                ("precision", C.c_int32), ("lr", C.c_float), ("momentum", C.c_float)]
+                ("precision", C.c_int32), ("lr", C.c_float), ("momentum", C.c_float),
+                ("mixing", C.POINTER(C.c_float))]
 
 
 class DdsError(RuntimeError):
@@ -65,6 +66,8 @@ def _load():
     lib.dds_param_count.restype = C.c_int64
     lib.dds_get_params.argtypes = [vp, C.c_int, vp, C.c_size_t, vp]
     lib.dds_set_params.argtypes = [vp, C.c_int, vp, C.c_size_t, vp]
+    lib.dds_get_params_replica.argtypes = [vp, C.c_int, C.c_int, vp, C.c_size_t, vp]
+    lib.dds_consensus_error.argtypes = [vp, C.POINTER(C.c_double), vp]
     lib.dds_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.c_float, vp]
     lib.dds_get_loss.argtypes = [vp, f32p, vp]
     lib.dds_step_count.argtypes = [vp]
@@ -103,7 +106,7 @@ def dds_schedule(K: int, delays: Optional[Sequence[int]], t: int) -> np.ndarray:
 class Spec:
     """Owns the ctypes arrays behind a dds_spec."""
 
-    def __init__(self, ops, bounds, in_shape, classes, batch, precision, lr, momentum):
+    def __init__(self, ops, bounds, in_shape, classes, batch, precision, lr, momentum, mixing=None):
         n = len(ops)
         self.layers = (dds_layer * n)()
         for i, op in enumerate(ops):
@@ -120,12 +123,17 @@ class Spec:
                     L.cin, L.cout, L.ksize, L.stride, L.pad = sc["cin"], sc["cout"], sc["k"], sc["stride"], sc["pad"]
         self.bounds = (C.c_int32 * len(bounds))(*bounds)
         self.K = len(bounds) - 1
+        # mixing: None (exact mean) or a W x W array, the matrix P of the communication graph
+        self.mixing = None
+        if mixing is not None:
+            flat = np.ascontiguousarray(np.asarray(mixing, dtype=np.float32)).ravel()
+            self.mixing = (C.c_float * flat.size)(*flat.tolist())
         self.c = dds_spec(n, self.layers, self.bounds, in_shape[0], in_shape[1], in_shape[2], classes, batch,
-                          PRECISION[precision], lr, momentum)
+                          PRECISION[precision], lr, momentum, self.mixing)
 
     @classmethod
-    def from_workload(cls, wl):
-        return cls(wl.ops, wl.bounds, wl.in_shape, wl.classes, wl.B, wl.precision, wl.lr, wl.momentum)
+    def from_workload(cls, wl, mixing=None):
+        return cls(wl.ops, wl.bounds, wl.in_shape, wl.classes, wl.B, wl.precision, wl.lr, wl.momentum, mixing)
 
 
 def dds_arena_bytes(spec: Spec, K: int, W: int, delays=None) -> int:
@@ -173,6 +181,18 @@ class Trainer:
         _check(lib.dds_get_params(self.ctx, module, dev.data_ptr(), n, self._stream()))
         self.torch.cuda.synchronize(self.device)
         return dev.cpu().numpy()
+
+    def dds_get_params_replica(self, module: int, replica: int) -> np.ndarray:
+        n = self.dds_param_count(module)
+        dev = self.torch.empty(n, dtype=self.torch.float32, device=self.device)
+        _check(lib.dds_get_params_replica(self.ctx, module, replica, dev.data_ptr(), n, self._stream()))
+        self.torch.cuda.synchronize(self.device)
+        return dev.cpu().numpy()
+
+    def dds_consensus_error(self) -> float:
+        v = C.c_double()
+        _check(lib.dds_consensus_error(self.ctx, C.byref(v), self._stream()))
+        return v.value
 
     def dds_step(self, xs, ys, lr: float = math.nan):
         """xs[s]: float32 CUDA tensor [B,C,H,W]; ys[s]: int32 CUDA tensor [B]."""

@@ -75,8 +75,9 @@ struct ParamLayer {
   int nsplit = 0;
   bool need_stash = false;
   float* partial = nullptr;
-  char* stash = nullptr;  // [R_k][Cin*RS*Coutpad] compute dtype
+  char* stash = nullptr;  // [copies][R_k][Cin*RS*Coutpad] compute dtype
   long long stash_elems = 0;
+  size_t stash_slot_bytes = 0;  // one snapshot, rounded up to 256 bytes
 };
 
 struct Node {
@@ -106,10 +107,11 @@ struct Module {
   std::vector<GradBuf> grads;
   size_t slot_bytes = 0;
   char* ring = nullptr;
-  long long n_master = 0;  // floats
-  float* master = nullptr;
-  float* momentum = nullptr;
-  char* work = nullptr;    // compute-precision copy (bf16 path)
+  long long n_master = 0;  // floats per weight copy
+  float* master = nullptr;    // [copies][n_master]
+  float* momentum = nullptr;  // [copies][n_master]
+  char* work = nullptr;       // compute-precision copy (bf16 path), [copies][n_master]
+  double* cons_dev = nullptr; // [2 * layers][W] squared distances to the mean (general mixing matrix only)
   // error mailbox written by module k0+1, read by this module
   int err_depth = 0;
   size_t err_bytes = 0;
@@ -156,6 +158,11 @@ struct dds_ctx {
   int64_t launches = 0;
   double gemm_flops = 0.0;
   size_t arena_used = 0;
+  // general mixing matrix (Section 2.3): `copies` = W weight copies per module instead of one
+  bool gossip = false;
+  int copies = 1;
+  std::vector<float> P;    // host, W x W
+  float* P_dev = nullptr;
   bool serial = false;  // DDS_SERIAL=1 in the environment at dds_create: modules run one after another on the
                         // caller's stream (per-kernel timing without other modules sharing the chip)
   // optional per-launch timing of the MFMA kernels (events on the launching stream)
@@ -462,9 +469,10 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
     for (Tensor& t : m.tensors)
       if (t.kind == T_TEMP) t.temp = A.take(t.bytes);
     for (GradBuf& g : m.grads) g.ptr = A.take(g.bytes);
-    m.master = (float*)A.take((size_t)m.n_master * 4);
-    if (c.mu != 0.f) m.momentum = (float*)A.take((size_t)m.n_master * 4);
-    if (c.dt == DT_BF16) m.work = A.take((size_t)m.n_master * es);
+    m.master = (float*)A.take((size_t)m.n_master * 4 * c.copies);
+    if (c.mu != 0.f) m.momentum = (float*)A.take((size_t)m.n_master * 4 * c.copies);
+    if (c.dt == DT_BF16) m.work = A.take((size_t)m.n_master * es * c.copies);
+    if (c.gossip) m.cons_dev = (double*)A.take(sizeof(double) * 2 * m.layers.size() * c.W);
     for (Node& nd : m.nodes) {
       if (nd.kind != N_CONV) continue;
       ParamLayer& L = m.layers[nd.layer];
@@ -484,7 +492,8 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
       L.partial = (float*)A.take((size_t)L.nsplit * L.pstride * 4);
       if (L.need_stash) {
         L.stash_elems = (long long)L.Cin * L.RS * L.Coutpad;
-        L.stash = A.take(align_up((size_t)L.stash_elems * es, 256) * m.R);
+        L.stash_slot_bytes = align_up((size_t)L.stash_elems * es, 256);
+        L.stash = A.take(L.stash_slot_bytes * m.R * c.copies);
       }
     }
     if (k0 < c.K - 1) {
@@ -499,16 +508,17 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
       nb_u += (int)((L.n + 1023) / 1024);
       if (L.need_stash) nb_s += L.RS * ((L.Cin + 63) / 64) * ((L.Coutpad + 63) / 64);  // 64 x 64 tiles per tap
     }
-    m.blocks_update = nb_u;
+    m.blocks_update = nb_u;  // per weight copy; the tables list copy 0 first, then copy 1, ...
     m.blocks_stash = nb_s;
-    m.descs_dev = (UpdateDesc*)A.take(sizeof(UpdateDesc) * m.layers.size());
-    m.map_update_dev = (int*)A.take(sizeof(int) * 2 * (nb_u > 0 ? nb_u : 1));
-    m.map_stash_dev = (int*)A.take(sizeof(int) * 2 * (nb_s > 0 ? nb_s : 1));
+    m.descs_dev = (UpdateDesc*)A.take(sizeof(UpdateDesc) * m.layers.size() * c.copies);
+    m.map_update_dev = (int*)A.take(sizeof(int) * 2 * (nb_u > 0 ? nb_u : 1) * c.copies);
+    m.map_stash_dev = (int*)A.take(sizeof(int) * 2 * (nb_s > 0 ? nb_s : 1) * c.copies);
   }
   c.label_depth = c.K + 2 * c.d[c.K - 1];
   c.labels = (int32_t*)A.take(sizeof(int32_t) * c.N * c.label_depth);
   c.loss = (float*)A.take(sizeof(float) * c.W);
   c.zeros = A.take(kZeroBytes);
+  if (c.gossip) c.P_dev = (float*)A.take(sizeof(float) * c.W * c.W);
   (void)sp;
   return DDS_OK;
 }
@@ -538,6 +548,22 @@ int build(dds_ctx& c, const dds_spec* sp, int K, int W, const int* delays) {
   c.in_w = sp->in_w;
   c.lr = sp->lr;
   c.mu = sp->momentum;
+  if (sp->mixing) {
+    // Section 2.3: P symmetric, doubly stochastic, entries in [0,1]
+    for (int i = 0; i < W; ++i) {
+      double row = 0.0;
+      for (int j = 0; j < W; ++j) {
+        const float v = sp->mixing[i * W + j];
+        if (!(v >= 0.f && v <= 1.f)) return fail(DDS_EINVAL, "mixing[%d][%d]=%g is outside [0,1]", i, j, (double)v);
+        if (std::fabs(v - sp->mixing[j * W + i]) > 1e-6f) return fail(DDS_EINVAL, "mixing matrix is not symmetric at (%d,%d)", i, j);
+        row += v;
+      }
+      if (std::fabs(row - 1.0) > 1e-5) return fail(DDS_EINVAL, "row %d of the mixing matrix sums to %g, not 1", i, row);
+    }
+    c.gossip = true;
+    c.copies = W;
+    c.P.assign(sp->mixing, sp->mixing + (size_t)W * W);
+  }
   c.mods.assign(K, Module());
   for (int k0 = 0; k0 < K; ++k0) {
     Module& m = c.mods[k0];
@@ -655,18 +681,26 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
     switch (nd.kind) {
       case N_CONV: {
         const ParamLayer& L = m.layers[nd.layer];
+        char* res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
+        char* bits = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
+        // one launch over all W*B images with the shared weights, or (general mixing matrix) one
+        // launch per data-group over its B images with its own weights
+        const int Nr = c.N / c.copies;
+        for (int r = 0; r < c.copies; ++r) {
+        const size_t e_in = (size_t)r * Nr * ti.H * ti.W * ti.Cpad, e_out = (size_t)r * Nr * to.H * to.W * to.Cpad;
+        const long long woff = (long long)r * m.n_master + L.off;
         ConvParams p{};
-        p.x = x;
-        p.w = c.dt == DT_BF16 ? (const void*)(m.work + (size_t)L.off * es) : (const void*)(m.master + L.off);
-        p.y = y;
-        p.bias = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
-        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
+        p.x = x + e_in * es;
+        p.w = c.dt == DT_BF16 ? (const void*)(m.work + (size_t)woff * es) : (const void*)(m.master + woff);
+        p.y = y + e_out * (nd.out_f32 ? 4 : es);
+        p.bias = m.master + woff + (long long)L.Cout * L.RS * L.Cinpad;
+        p.res = res ? res + e_out * es : nullptr;
         p.mask = nullptr;
-        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
+        p.bits_out = bits ? bits + e_out / 8 : nullptr;
         p.zeros = c.zeros;
-        p.Nimg = c.N; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
+        p.Nimg = Nr; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
         p.Ho = to.H; p.Wo = to.W;
-        p.M = c.N * to.H * to.W;
+        p.M = Nr * to.H * to.W;
         p.Nout = L.Cout;
         p.ldy = to.Cpad;
         p.R = L.R; p.S = L.R; p.stride = L.stride; p.pad = L.pad;
@@ -679,6 +713,8 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
           ProfScope ps(c, s, 0, 2.0 * p.M * L.Cout * L.Cin * L.RS);
           ps.cls += 3 * launch_conv(c.dt, p, s);
         }
+        }
+        c.launches += c.copies - 1;
         break;
       }
       case N_MAXPOOL:
@@ -706,20 +742,25 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
     switch (nd.kind) {
       case N_CONV: {
         const ParamLayer& L = m.layers[nd.layer];
-        const int ldg = nd.out_f32 ? to.Cpad : to.Cpad;
+        const int ldg = to.Cpad;
+        const int Nr = c.N / c.copies, q = L.nsplit / c.copies;  // nsplit is a multiple of W
+        char* addend = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
+        char* maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, b) : nullptr;
+        for (int r = 0; r < c.copies; ++r) {
+        const size_t e_in = (size_t)r * Nr * ti.H * ti.W * ti.Cpad, e_out = (size_t)r * Nr * to.H * to.W * ldg;
         WgradParams w{};
-        w.dy = gout;
-        w.x = x;
-        w.partial = L.partial;
+        w.dy = gout + e_out * es;
+        w.x = x + e_in * es;
+        w.partial = L.partial + (size_t)r * q * L.pstride;
         w.zeros = c.zeros;
-        w.Nimg = c.N; w.H = ti.H; w.W = ti.W; w.Cx = ti.Cpad; w.Ho = to.H; w.Wo = to.W;
+        w.Nimg = Nr; w.H = ti.H; w.W = ti.W; w.Cx = ti.Cpad; w.Ho = to.H; w.Wo = to.W;
         w.Mout = L.Cout;
         w.ldy = ldg;
         w.R = L.R; w.S = L.R; w.stride = L.stride; w.pad = L.pad;
         w.NK = L.RS * L.Cinpad;
-        w.P = c.N * to.H * to.W;
-        w.nsplit = L.nsplit;
-        w.pix_per_split = w.P / L.nsplit;
+        w.P = Nr * to.H * to.W;
+        w.nsplit = q;
+        w.pix_per_split = w.P / q;
         w.Pl = L.pstride;
         w.alpha = nd.alpha;
         {
@@ -729,24 +770,24 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
         ++c.launches;
         if (nd.gin != G_NONE) {
           ConvParams p{};
-          p.x = gout;
-          p.w = L.stash + (size_t)slot * align_up((size_t)L.stash_elems * es, 256);
-          p.y = gin;
+          p.x = gout + e_out * es;
+          p.w = L.stash + ((size_t)r * m.R + slot) * L.stash_slot_bytes;
+          p.y = gin + e_in * es;
           p.bias = nullptr;
-          p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
+          p.res = addend ? addend + e_in * es : nullptr;
           if (nd.fold_sc >= 0) {
             const Node& sc = m.nodes[nd.fold_sc];
             const ParamLayer& Ls = m.layers[sc.layer];
-            p.x2 = gptr(c, m, sc.gout, t);
-            p.w2 = Ls.stash + (size_t)slot * align_up((size_t)Ls.stash_elems * es, 256);
             p.Cx2 = m.tensors[sc.out].Cpad;
+            p.x2 = gptr(c, m, sc.gout, t) + (size_t)r * Nr * to.H * to.W * p.Cx2 * es;
+            p.w2 = Ls.stash + ((size_t)r * m.R + slot) * Ls.stash_slot_bytes;
           }
-          p.maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, b) : nullptr;
-          p.mask = nd.mask_in && !p.maskbits ? x : nullptr;
+          p.maskbits = maskbits ? maskbits + e_in / 8 : nullptr;
+          p.mask = nd.mask_in && !maskbits ? x + e_in * es : nullptr;
           p.zeros = c.zeros;
-          p.Nimg = c.N; p.H = to.H; p.W = to.W; p.Cx = ldg;
+          p.Nimg = Nr; p.H = to.H; p.W = to.W; p.Cx = ldg;
           p.Ho = ti.H; p.Wo = ti.W;
-          p.M = c.N * ti.H * ti.W;
+          p.M = Nr * ti.H * ti.W;
           p.Nout = L.Cin;
           p.ldy = ti.Cpad;
           p.R = L.R; p.S = L.R; p.stride = L.stride; p.pad = L.pad;
@@ -760,6 +801,7 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
             ps.cls += 3 * launch_conv(c.dt, p, s);
           }
           ++c.launches;
+        }
         }
         break;
       }
@@ -782,29 +824,36 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
 int upload_tables(dds_ctx& c) {
   const int es = dtype_size(c.dt);
   for (Module& m : c.mods) {
-    std::vector<UpdateDesc> descs(m.layers.size());
+    // one descriptor per (weight copy, layer); copy r sums only its own data-group's splits
+    const size_t nl = m.layers.size();
+    std::vector<UpdateDesc> descs(nl * c.copies);
     std::vector<int> mu, ms;
-    for (size_t li = 0; li < m.layers.size(); ++li) {
+    for (int r = 0; r < c.copies; ++r)
+    for (size_t li = 0; li < nl; ++li) {
       const ParamLayer& L = m.layers[li];
-      UpdateDesc& d = descs[li];
-      d.master = m.master + L.off;
-      d.momentum = m.momentum ? m.momentum + L.off : nullptr;
-      d.partial = L.partial;
-      d.work = m.work ? (void*)(m.work + (size_t)L.off * es) : nullptr;
-      d.stash = L.stash;
-      d.stash_slot_elems = (long long)(align_up((size_t)L.stash_elems * es, 256) / es);
+      const int di = (int)(r * nl + li);
+      const long long woff = (long long)r * m.n_master + L.off;
+      const int q = L.nsplit / c.copies;
+      UpdateDesc& d = descs[di];
+      d.master = m.master + woff;
+      d.momentum = m.momentum ? m.momentum + woff : nullptr;
+      d.partial = L.partial + (size_t)r * q * L.pstride;
+      d.work = m.work ? (void*)(m.work + (size_t)woff * es) : nullptr;
+      d.stash = L.stash ? L.stash + (size_t)r * m.R * L.stash_slot_bytes : nullptr;
+      d.stash_slot_elems = (long long)(L.stash_slot_bytes / es);
       d.n = L.n;
       d.pstride = L.pstride;
-      d.nsplit = L.nsplit;
+      d.nsplit = q;
       d.Cout = L.Cout; d.RS = L.RS; d.Cinpad = L.Cinpad; d.Cin = L.Cin; d.Coutpad = L.Coutpad;
-      for (int b = 0; b < (int)((L.n + 1023) / 1024); ++b) { mu.push_back((int)li); mu.push_back(b); }
+      for (int b = 0; b < (int)((L.n + 1023) / 1024); ++b) { mu.push_back(di); mu.push_back(b); }
       if (L.need_stash)
-        for (int b = 0; b < L.RS * ((L.Cin + 63) / 64) * ((L.Coutpad + 63) / 64); ++b) { ms.push_back((int)li); ms.push_back(b); }
+        for (int b = 0; b < L.RS * ((L.Cin + 63) / 64) * ((L.Coutpad + 63) / 64); ++b) { ms.push_back(di); ms.push_back(b); }
     }
     if (!descs.empty()) HIP_TRY(hipMemcpy(m.descs_dev, descs.data(), sizeof(UpdateDesc) * descs.size(), hipMemcpyHostToDevice));
     if (!mu.empty()) HIP_TRY(hipMemcpy(m.map_update_dev, mu.data(), sizeof(int) * mu.size(), hipMemcpyHostToDevice));
     if (!ms.empty()) HIP_TRY(hipMemcpy(m.map_stash_dev, ms.data(), sizeof(int) * ms.size(), hipMemcpyHostToDevice));
   }
+  if (c.gossip) HIP_TRY(hipMemcpy(c.P_dev, c.P.data(), sizeof(float) * c.P.size(), hipMemcpyHostToDevice));
   return DDS_OK;
 }
 
@@ -931,30 +980,59 @@ int64_t dds_step_count(const dds_ctx* c) { return c ? c->t : (int64_t)fail(DDS_E
 int64_t dds_launches_last_step(const dds_ctx* c) { return c ? c->launches : (int64_t)fail(DDS_EINVAL, "null ctx"); }
 double dds_gemm_flops_per_step(const dds_ctx* c) { return c ? c->gemm_flops : 0.0; }
 
-static int params_io(dds_ctx* c, int module, float* buf, size_t n_floats, void* stream, bool set) {
+static int params_io(dds_ctx* c, int module, int replica, float* buf, size_t n_floats, void* stream, bool set) {
   if (!c || module < 0 || module >= c->K || !buf) return fail(DDS_EINVAL, "bad ctx / module / pointer");
+  if (replica < 0 || replica >= c->W) return fail(DDS_EINVAL, "replica %d out of range [0,%d)", replica, c->W);
   Module& m = c->mods[module];
+  const long long roff = c->gossip ? (long long)replica * m.n_master : 0;
   if ((long long)n_floats != m.canon_params)
     return fail(DDS_EINVAL, "module %d has %lld parameters, caller passed %zu", module, m.canon_params, n_floats);
   hipStream_t s = (hipStream_t)stream;
   size_t off = 0;
   for (ParamLayer& L : m.layers) {
-    launch_param_permute(buf + off, m.master + L.off, L.Cout, L.Cin, L.RS, L.Cinpad, set ? 1 : 0, s);
+    launch_param_permute(buf + off, m.master + roff + L.off, L.Cout, L.Cin, L.RS, L.Cinpad, set ? 1 : 0, s);
     off += (size_t)L.Cout * L.Cin * L.RS + L.Cout;
   }
-  if (set) {
-    if (m.momentum) launch_fill_zero(m.momentum, (size_t)m.n_master * 4, s);
-    launch_recast(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, s);
-    for (int slot = 0; slot < m.R; ++slot) launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash, slot, s);
+  if (set) {  // always called with replica 0: every data-group starts from the same weights
+    for (int r = 1; r < c->copies; ++r)
+      HIP_TRY(hipMemcpyAsync(m.master + (size_t)r * m.n_master, m.master, (size_t)m.n_master * 4, hipMemcpyDeviceToDevice, s));
+    if (m.momentum) launch_fill_zero(m.momentum, (size_t)m.n_master * 4 * c->copies, s);
+    launch_recast(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update * c->copies, s);
+    for (int slot = 0; slot < m.R; ++slot)
+      launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, slot, s);
   }
   HIP_TRY(hipGetLastError());
   return DDS_OK;
 }
 
-int dds_get_params(dds_ctx* c, int module, float* dst, size_t n, void* stream) { return params_io(c, module, dst, n, stream, false); }
+int dds_get_params(dds_ctx* c, int module, float* dst, size_t n, void* stream) { return params_io(c, module, 0, dst, n, stream, false); }
+int dds_get_params_replica(dds_ctx* c, int module, int replica, float* dst, size_t n, void* stream) {
+  return params_io(c, module, replica, dst, n, stream, false);
+}
+
+int dds_consensus_error(dds_ctx* c, double* host_out, void* stream) {
+  if (!c || !host_out) return fail(DDS_EINVAL, "dds_consensus_error: null argument");
+  *host_out = 0.0;
+  if (!c->gossip) return DDS_OK;
+  hipStream_t s = (hipStream_t)stream;
+  double worst = 0.0;
+  std::vector<double> host;
+  for (Module& m : c->mods) {
+    if (m.layers.empty()) continue;
+    const size_t n = 2 * m.layers.size() * c->W;
+    launch_consensus(m.descs_dev, (int)m.layers.size(), c->W, m.n_master, m.cons_dev, s);
+    HIP_TRY(hipGetLastError());
+    host.resize(n);
+    HIP_TRY(hipMemcpyAsync(host.data(), m.cons_dev, n * sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    for (double v : host) worst = v > worst ? v : worst;
+  }
+  *host_out = std::sqrt(worst);
+  return DDS_OK;
+}
 int dds_set_params(dds_ctx* c, int module, const float* src, size_t n, void* stream) {
   if (c && c->t != 0) return fail(DDS_EINVAL, "dds_set_params is only valid before the first step");
-  return params_io(c, module, (float*)src, n, stream, true);
+  return params_io(c, module, 0, (float*)src, n, stream, true);
 }
 
 int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float lr, void* stream) {
@@ -1008,8 +1086,15 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
     }
     if (b >= 0) {
       run_backward(*c, m, t, b, s);
-      launch_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->W, step, c->mu, s);
-      launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash, (int)((t + 1) % m.R), s);
+      if (!c->gossip) {
+        launch_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->W, step, c->mu, s);
+      } else {
+        // u_r = w_r - lr * direction_r for every data-group (its own splits, no averaging), then the mixing step
+        launch_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update * c->W, 1, step, c->mu, s);
+        launch_mix(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->P_dev, c->W, m.n_master, s);
+        ++c->launches;
+      }
+      launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, (int)((t + 1) % m.R), s);
       c->launches += 2;
     }
     if (multi) {

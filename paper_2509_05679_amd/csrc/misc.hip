@@ -321,6 +321,63 @@ __global__ __launch_bounds__(256) void recast_kernel(const UpdateDesc* descs, co
   }
 }
 
+// Mixing step of Section 3.3 with a general matrix P: the master arrays of the W data-groups
+// hold u_r = w_r - lr * direction_r (left there by update_kernel, one descriptor per data-group);
+// this kernel replaces them by w_s = sum_r P[s][r] * u_r, r ascending, in fp32, and refreshes the
+// compute-precision copies. descs / block_map: data-group 0's entries; data-group r's arrays lie
+// rep_stride elements further per step of r. One thread owns an element in all W copies, so the
+// update is in place.
+template <typename T>
+__global__ __launch_bounds__(256) void mix_kernel(const UpdateDesc* descs, const int* block_map, const float* P, int W,
+                                                  long long rep_stride) {
+  const UpdateDesc d = descs[block_map[2 * blockIdx.x]];
+  const long long blk0 = (long long)block_map[2 * blockIdx.x + 1] * 1024;
+  for (int it = 0; it < 4; ++it) {
+    const long long i = blk0 + it * 256 + threadIdx.x;
+    if (i >= d.n) return;
+    float u[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) u[r] = r < W ? d.master[(long long)r * rep_stride + i] : 0.f;
+    for (int s = 0; s < W; ++s) {
+      float a = 0.f;
+#pragma unroll
+      for (int r = 0; r < 32; ++r)
+        if (r < W) a = fmaf(P[s * W + r], u[r], a);
+      d.master[(long long)s * rep_stride + i] = a;
+      if (d.work) {
+        if (sizeof(T) == 2) ((uint16_t*)d.work)[(long long)s * rep_stride + i] = f2bf(a);
+        else ((float*)d.work)[(long long)s * rep_stride + i] = a;
+      }
+    }
+  }
+}
+
+// Disagreement between data-groups (experiment section): workgroup (tensor, s) accumulates
+// sum_i (w_s[i] - mean_r w_r[i])^2 in fp64 over one parameter tensor (tensor = 2*layer + {0: weight,
+// 1: bias}) and writes it to out[tensor * W + s]; the host takes the square root of the maximum.
+__global__ __launch_bounds__(256) void consensus_kernel(const UpdateDesc* descs, int W, long long rep_stride, double* out) {
+  const UpdateDesc d = descs[blockIdx.x >> 1];
+  const int s = blockIdx.y;
+  const long long nw = d.n - d.Cout;
+  const long long lo = (blockIdx.x & 1) ? nw : 0, hi = (blockIdx.x & 1) ? d.n : nw;
+  double acc = 0.0;
+  for (long long i = lo + threadIdx.x; i < hi; i += 256) {
+    double mean = 0.0;
+    for (int r = 0; r < W; ++r) mean += (double)d.master[(long long)r * rep_stride + i];
+    mean /= (double)W;
+    const double e = (double)d.master[(long long)s * rep_stride + i] - mean;
+    acc += e * e;
+  }
+  __shared__ double red[256];
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[(size_t)blockIdx.x * W + s] = red[0];
+}
+
 // transposed snapshot: stash[slot][c][tap][kpad] <- master[k][tap][cpad], zero for k >= Cout.
 // One workgroup moves a 64(k) x 64(c) tile of one tap through LDS so that both the reads
 // (64 consecutive c) and the writes (64 consecutive k) are whole cache lines.
@@ -439,6 +496,17 @@ void launch_recast(int dt, const UpdateDesc* descs, const int* block_map, int to
 void launch_stash(int dt, const UpdateDesc* descs, const int* block_map, int total_blocks, int slot, hipStream_t s) {
   if (total_blocks <= 0) return;
   DDS_DISPATCH(dt, stash_kernel, <<<total_blocks, 256, 0, s>>>(descs, block_map, slot));
+}
+
+void launch_mix(int dt, const UpdateDesc* descs, const int* block_map, int total_blocks, const float* P, int W,
+                long long rep_stride, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  DDS_DISPATCH(dt, mix_kernel, <<<total_blocks, 256, 0, s>>>(descs, block_map, P, W, rep_stride));
+}
+
+void launch_consensus(const UpdateDesc* descs, int nlayers, int W, long long rep_stride, double* out, hipStream_t s) {
+  if (nlayers <= 0) return;
+  consensus_kernel<<<dim3(2 * nlayers, W), 256, 0, s>>>(descs, W, rep_stride, out);
 }
 
 void launch_param_permute(const float* canon, float* internal, int Cout, int Cin, int RS, int Cinpad, int to_internal,

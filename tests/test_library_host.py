@@ -107,6 +107,25 @@ def test_spec_validation_errors():
         P.dds_arena_bytes(P.Spec(good.ops, [0, 3, 3], good.in_shape, 10, 4, "f32", 0.1, 0.0), 2, 1)
 
 
+def test_mixing_matrix_validation_and_arena_growth():
+    from dds_inputs.configs import complete_mixing, ring_mixing
+    wl = tiny_resnet(K=2, W=4)
+    shared = P.dds_arena_bytes(P.Spec.from_workload(wl), 2, 4)
+    own = P.dds_arena_bytes(P.Spec.from_workload(wl, ring_mixing(4, 0.3)), 2, 4)
+    assert own > shared  # W weight copies, momenta and snapshot rings instead of one
+    assert P.dds_arena_bytes(P.Spec.from_workload(wl, complete_mixing(4)), 2, 4) == own
+    ring = np.array(ring_mixing(4, 0.3))
+    assert np.allclose(ring.sum(0), 1) and np.allclose(ring.sum(1), 1) and np.array_equal(ring, ring.T)
+    assert np.array_equal(ring, fdg.gossip_matrix(4, [(0, 1), (1, 2), (2, 3), (3, 0)], 0.3).numpy())
+    bad_rows = ring.copy(); bad_rows[0, 0] += 0.1
+    asym = ring.copy(); asym[0, 1] += 0.1; asym[0, 0] -= 0.1
+    neg = np.array(ring_mixing(4, 0.6))  # diagonal 1 - 1.2 < 0
+    for bad in (bad_rows, asym, neg):
+        with pytest.raises(P.DdsError) as e:
+            P.dds_arena_bytes(P.Spec.from_workload(wl, bad), 2, 4)
+        assert e.value.code == P.DDS_EINVAL
+
+
 def test_no_gpu_means_a_loud_failure_not_a_fallback():
     import torch
     if torch.cuda.is_available():
