@@ -681,26 +681,22 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
     switch (nd.kind) {
       case N_CONV: {
         const ParamLayer& L = m.layers[nd.layer];
-        char* res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
-        char* bits = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
-        // one launch over all W*B images with the shared weights, or (general mixing matrix) one
-        // launch per data-group over its B images with its own weights
-        const int Nr = c.N / c.copies;
-        for (int r = 0; r < c.copies; ++r) {
-        const size_t e_in = (size_t)r * Nr * ti.H * ti.W * ti.Cpad, e_out = (size_t)r * Nr * to.H * to.W * to.Cpad;
-        const long long woff = (long long)r * m.n_master + L.off;
         ConvParams p{};
-        p.x = x + e_in * es;
-        p.w = c.dt == DT_BF16 ? (const void*)(m.work + (size_t)woff * es) : (const void*)(m.master + woff);
-        p.y = y + e_out * (nd.out_f32 ? 4 : es);
-        p.bias = m.master + woff + (long long)L.Cout * L.RS * L.Cinpad;
-        p.res = res ? res + e_out * es : nullptr;
+        p.x = x;
+        p.w = c.dt == DT_BF16 ? (const void*)(m.work + (size_t)L.off * es) : (const void*)(m.master + L.off);
+        p.y = y;
+        p.bias = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
+        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
         p.mask = nullptr;
-        p.bits_out = bits ? bits + e_out / 8 : nullptr;
+        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
         p.zeros = c.zeros;
-        p.Nimg = Nr; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
+        p.Nimg = c.N; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
         p.Ho = to.H; p.Wo = to.W;
-        p.M = Nr * to.H * to.W;
+        p.M = c.N * to.H * to.W;
+        // general mixing matrix: data-group r's images meet data-group r's weights
+        p.nrep = c.copies;
+        p.w_rep = m.n_master * es;
+        p.bias_rep = m.n_master;
         p.Nout = L.Cout;
         p.ldy = to.Cpad;
         p.R = L.R; p.S = L.R; p.stride = L.stride; p.pad = L.pad;
@@ -713,8 +709,6 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
           ProfScope ps(c, s, 0, 2.0 * p.M * L.Cout * L.Cin * L.RS);
           ps.cls += 3 * launch_conv(c.dt, p, s);
         }
-        }
-        c.launches += c.copies - 1;
         break;
       }
       case N_MAXPOOL:
@@ -730,7 +724,6 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
 
 void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
   const int slot = (int)(((t - 2 * m.d) % m.R + m.R) % m.R);
-  const int es = dtype_size(c.dt);
   for (int ni = (int)m.nodes.size() - 1; ni >= 0; --ni) {
     const Node& nd = m.nodes[ni];
     if (nd.kind == N_CE) continue;  // dlogits were produced by the loss kernel
@@ -743,24 +736,21 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
       case N_CONV: {
         const ParamLayer& L = m.layers[nd.layer];
         const int ldg = to.Cpad;
-        const int Nr = c.N / c.copies, q = L.nsplit / c.copies;  // nsplit is a multiple of W
-        char* addend = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
-        char* maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, b) : nullptr;
-        for (int r = 0; r < c.copies; ++r) {
-        const size_t e_in = (size_t)r * Nr * ti.H * ti.W * ti.Cpad, e_out = (size_t)r * Nr * to.H * to.W * ldg;
+        // The weight gradient reads no weights: one launch serves every data-group, and since no
+        // split mixes two of them, data-group r's gradient is the sum of its own nsplit / W splits.
         WgradParams w{};
-        w.dy = gout + e_out * es;
-        w.x = x + e_in * es;
-        w.partial = L.partial + (size_t)r * q * L.pstride;
+        w.dy = gout;
+        w.x = x;
+        w.partial = L.partial;
         w.zeros = c.zeros;
-        w.Nimg = Nr; w.H = ti.H; w.W = ti.W; w.Cx = ti.Cpad; w.Ho = to.H; w.Wo = to.W;
+        w.Nimg = c.N; w.H = ti.H; w.W = ti.W; w.Cx = ti.Cpad; w.Ho = to.H; w.Wo = to.W;
         w.Mout = L.Cout;
         w.ldy = ldg;
         w.R = L.R; w.S = L.R; w.stride = L.stride; w.pad = L.pad;
         w.NK = L.RS * L.Cinpad;
-        w.P = Nr * to.H * to.W;
-        w.nsplit = q;
-        w.pix_per_split = w.P / q;
+        w.P = c.N * to.H * to.W;
+        w.nsplit = L.nsplit;
+        w.pix_per_split = w.P / L.nsplit;
         w.Pl = L.pstride;
         w.alpha = nd.alpha;
         {
@@ -770,24 +760,27 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
         ++c.launches;
         if (nd.gin != G_NONE) {
           ConvParams p{};
-          p.x = gout + e_out * es;
-          p.w = L.stash + ((size_t)r * m.R + slot) * L.stash_slot_bytes;
-          p.y = gin + e_in * es;
+          p.x = gout;
+          p.w = L.stash + (size_t)slot * L.stash_slot_bytes;
+          p.y = gin;
           p.bias = nullptr;
-          p.res = addend ? addend + e_in * es : nullptr;
+          p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
+          p.nrep = c.copies;  // data-group r back-propagates through its own snapshot
+          p.w_rep = (long long)m.R * L.stash_slot_bytes;
           if (nd.fold_sc >= 0) {
             const Node& sc = m.nodes[nd.fold_sc];
             const ParamLayer& Ls = m.layers[sc.layer];
+            p.x2 = gptr(c, m, sc.gout, t);
+            p.w2 = Ls.stash + (size_t)slot * Ls.stash_slot_bytes;
             p.Cx2 = m.tensors[sc.out].Cpad;
-            p.x2 = gptr(c, m, sc.gout, t) + (size_t)r * Nr * to.H * to.W * p.Cx2 * es;
-            p.w2 = Ls.stash + ((size_t)r * m.R + slot) * Ls.stash_slot_bytes;
+            p.w2_rep = (long long)m.R * Ls.stash_slot_bytes;
           }
-          p.maskbits = maskbits ? maskbits + e_in / 8 : nullptr;
-          p.mask = nd.mask_in && !maskbits ? x + e_in * es : nullptr;
+          p.maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, b) : nullptr;
+          p.mask = nd.mask_in && !p.maskbits ? x : nullptr;
           p.zeros = c.zeros;
-          p.Nimg = Nr; p.H = to.H; p.W = to.W; p.Cx = ldg;
+          p.Nimg = c.N; p.H = to.H; p.W = to.W; p.Cx = ldg;
           p.Ho = ti.H; p.Wo = ti.W;
-          p.M = Nr * ti.H * ti.W;
+          p.M = c.N * ti.H * ti.W;
           p.Nout = L.Cin;
           p.ldy = ti.Cpad;
           p.R = L.R; p.S = L.R; p.stride = L.stride; p.pad = L.pad;
@@ -801,7 +794,6 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
             ps.cls += 3 * launch_conv(c.dt, p, s);
           }
           ++c.launches;
-        }
         }
         break;
       }

@@ -318,7 +318,8 @@ __device__ __forceinline__ void epilogue_tile(const ConvParams& p, const f32x16_
 // s = cw + pad (mod 2), so a workgroup walks just those taps: on average 2.25 of the 9 taps
 // of a 3x3 kernel, and 1 class in 4 has any tap at all for a 1x1 kernel.
 template <typename T, int BM, int BN, int WM, int WN, int BKB, bool DGRAD, bool S2 = false>
-__global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int tiles_per_class) {
+__global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p_, int tiles_per_class) {
+  ConvParams p = p_;
   constexpr int ES = sizeof(T);
   constexpr int CE = 16 / ES;     // elements per 16-byte chunk
   constexpr int BKE = BKB / ES;   // k elements per tile
@@ -337,6 +338,13 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p, int til
   const int Hc = (p.Ho - ch + 1) >> 1, Wc = (p.Wo - cw + 1) >> 1;  // pixels of this class per image column / row
   const int Mc = S2 ? p.Nimg * Hc * Wc : p.M;
   const int m0 = (S2 ? blockIdx.x - cls * tiles_per_class : blockIdx.x) * BM, n0 = blockIdx.y * BN;
+  if (p.nrep > 1) {  // the launcher made sure that a tile never straddles two data-groups
+    const int rows_per_rep = Mc / p.nrep;
+    const int r = min(m0 / rows_per_rep, p.nrep - 1);
+    p.w = (const char*)p.w + (size_t)r * p.w_rep;
+    if (p.bias) p.bias += (size_t)r * p.bias_rep;
+    if (p.w2) p.w2 = (const char*)p.w2 + (size_t)r * p.w2_rep;
+  }
   const int chunk = tid % CPR, rbase = tid / CPR;
   const int sh = p.stride - 1;  // stride is 1 or 2
   // row of the tile -> output pixel (image, oh, ow) and its flat index
@@ -569,7 +577,8 @@ struct DmaGeom {
 };
 
 template <typename T, int BM, int BN, int WM, int WN, int PS, int KB>
-__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) == 4 ? 2 : 1) void conv3x3_dma_kernel(ConvParams p, DmaGeom dg) {
+__global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) == 4 ? 2 : 1) void conv3x3_dma_kernel(ConvParams p_, DmaGeom dg) {
+  ConvParams p = p_;
   constexpr int ES = sizeof(T);
   constexpr int NW = (BM / WM) * (BN / WN);  // waves per workgroup (each owns a WM x WN sub-tile)
   constexpr int FROWS = 1024 / KB;     // LDS rows per wave fill (KB = bytes of channels per row: 64 or 128)
@@ -601,6 +610,11 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) =
   const int th_idx = tin / g.tiles_w, tw_idx = tin - th_idx * g.tiles_w;
   const int img0 = grp * g.imgs, h0 = th_idx << g.th_log, w0 = tw_idx << g.tw_log;
   const int n0 = blockIdx.y * BN;
+  if (p.nrep > 1) {  // the launcher made sure that the images of a tile belong to one data-group
+    const int r = min(img0 / (p.Nimg / p.nrep), p.nrep - 1);
+    p.w = (const char*)p.w + (size_t)r * p.w_rep;
+    if (p.bias) p.bias += (size_t)r * p.bias_rep;
+  }
   const int TWm = (1 << g.tw_log) - 1, THm = (1 << g.th_log) - 1;
   const int nchunks = (p.Cx * ES) / KB;
   const size_t pixbytes = (size_t)p.Cx * ES;
@@ -1365,8 +1379,56 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 
+// Problem of data-group r alone (see ConvParams::nrep): its images, outputs and weights.
+template <typename T>
+ConvParams replica_slice(const ConvParams& p, int r) {
+  constexpr size_t ES = sizeof(T);
+  ConvParams q = p;
+  const size_t Nr = (size_t)(p.Nimg / p.nrep);
+  const size_t in_pix = r * Nr * p.H * p.W, out_el = r * Nr * p.Ho * p.Wo * p.ldy;
+  q.x = (const char*)p.x + in_pix * p.Cx * ES;
+  q.y = (char*)p.y + out_el * (p.out_f32 ? 4 : ES);
+  if (p.res) q.res = (const char*)p.res + out_el * ES;
+  if (p.mask) q.mask = (const char*)p.mask + out_el * ES;
+  if (p.bits_out) q.bits_out = (char*)p.bits_out + out_el / 8;
+  if (p.maskbits) q.maskbits = (const char*)p.maskbits + out_el / 8;
+  if (p.x2) q.x2 = (const char*)p.x2 + in_pix * p.Cx2 * ES;
+  q.w = (const char*)p.w + (size_t)r * p.w_rep;
+  if (p.w2) q.w2 = (const char*)p.w2 + (size_t)r * p.w2_rep;
+  if (p.bias) q.bias = p.bias + (size_t)r * p.bias_rep;
+  q.Nimg = (int)Nr;
+  q.M = p.M / p.nrep;
+  q.nrep = 1;
+  return q;
+}
+
+// True if no tile of any kernel variant (at most 256 rows) can hold pixels of two data-groups.
+inline bool replicas_tile_aligned(const ConvParams& p) {
+  const int Nr = p.Nimg / p.nrep;
+  if (p.dgrad && p.stride == 2) {  // rows are enumerated per parity class of the output grid
+    for (int cls = 0; cls < 4; ++cls) {
+      const int Hc = (p.Ho - (cls >> 1) + 1) >> 1, Wc = (p.Wo - (cls & 1) + 1) >> 1;
+      if ((Nr * Hc * Wc) % 256 != 0) return false;
+    }
+  }
+  return (Nr * p.Ho * p.Wo) % 256 == 0;
+}
+
+template <typename T>
+int launch_conv_one(const ConvParams& p, hipStream_t s);
+
 template <typename T>
 int launch_conv_t(const ConvParams& p, hipStream_t s) {
+  if (p.nrep > 1 && (p.Nimg % p.nrep != 0 || !replicas_tile_aligned(p))) {
+    int family = 1;  // one launch per data-group
+    for (int r = 0; r < p.nrep; ++r) family &= launch_conv_one<T>(replica_slice<T>(p, r), s);
+    return family;
+  }
+  return launch_conv_one<T>(p, s);
+}
+
+template <typename T>
+int launch_conv_one(const ConvParams& p, hipStream_t s) {
   constexpr int BKB = 64;
   if (launch_dma<T>(p, s)) return 1;
   // dgrad of a stride-2 convolution: workgroups per parity class (class (0,0) is the largest)

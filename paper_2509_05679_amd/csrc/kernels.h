@@ -53,6 +53,11 @@ struct ConvParams {
   int relu;
   int out_f32;        // y is fp32 regardless of T (logits)
   int dgrad;
+  // Data-groups with weights of their own (general mixing matrix): the Nimg images are nrep equal
+  // groups of consecutive images and group r multiplies by w + r*w_rep bytes, adds bias + r*bias_rep
+  // floats and (folded shortcut) uses w2 + r*w2_rep bytes. nrep <= 1: one weight set for all images.
+  int nrep;
+  long long w_rep, w2_rep, bias_rep;
 };
 
 // Weight-gradient GEMM with split reduction:
