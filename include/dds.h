@@ -145,6 +145,18 @@ int dds_consensus_error(dds_ctx* ctx, double* host_out, void* hip_stream);
 int dds_step(dds_ctx* ctx, const float* const* x_device, const int32_t* const* y_device, float lr,
              void* hip_stream);
 
+/* Step-size rules of the experiment section and of the diminishing step-size section, for
+ * callers that want eta_t computed the paper's way (pure host function, no GPU needed):
+ *   DDS_ETA_CONSTANT     Strategy I : eta_t = eta0 for all t (the paper uses eta0 = 0.1)
+ *   DDS_ETA_PIECEWISE    Strategy II: eta0 while t <= 15000, eta0/10 while t <= 30000, eta0/100
+ *                        while t <= 40000, eta0/1000 after (0.1, 0.01, 0.001, 0.0001 for eta0 = 0.1)
+ *   DDS_ETA_DIMINISHING  eta_t = eta0 / (t + 1)
+ * Returns eta_t, or NaN for an unknown rule or t < 0. dds_step's lr multiplies the mean of the
+ * data-groups' mean gradients: with W equal partitions the paper's update corresponds to
+ * lr = eta_t / W. */
+enum { DDS_ETA_CONSTANT = 1, DDS_ETA_PIECEWISE = 2, DDS_ETA_DIMINISHING = 3 };
+float dds_step_size(int rule, int64_t t, float eta0);
+
 /* Mean loss of the mini-batch the last module forwarded in the latest step (sampled
  * K-1 iterations earlier): mean over each replica's B samples, then over replicas.
  * Synchronises stream. DDS_EINVAL if no loss exists yet (fewer than K steps). */

@@ -79,6 +79,25 @@ def schedule(t: int, K: int, d: Optional[Sequence[int]] = None) -> List[dict]:
     return out
 
 
+# ----------------------------------------------------------------------------- step sizes
+def step_size(rule: str, t: int, eta0: float = 0.1) -> float:
+    """eta_t of the experiment section (Strategy I "constant", Strategy II "piecewise") and of
+    the diminishing step-size section ("diminishing": eta0 / (t + 1))."""
+    if rule == "constant":
+        return eta0
+    if rule == "piecewise":
+        if t <= 15000:
+            return eta0
+        if t <= 30000:
+            return eta0 * 0.1
+        if t <= 40000:
+            return eta0 * 0.01
+        return eta0 * 0.001
+    if rule == "diminishing":
+        return eta0 / (t + 1)
+    raise ValueError(rule)
+
+
 # ----------------------------------------------------------------------------- graphs
 def gossip_matrix(S: int, edges: Sequence[tuple], alpha: float) -> torch.Tensor:
     """Weighted matrix of a communication graph: alpha on edges, 1 - degree*alpha on

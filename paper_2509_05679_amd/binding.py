@@ -23,7 +23,7 @@ OPS = {"conv": 1, "linear": 2, "relu": 3, "maxpool2": 4, "gap": 5, "res_begin": 
        "softmax_ce": 8}
 PRECISION = {"f32": 0, "bf16": 1}
 
-EXPORTS = ["dds_schedule", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
+EXPORTS = ["dds_schedule", "dds_step_size", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
            "dds_get_params", "dds_set_params", "dds_get_params_replica", "dds_consensus_error", "dds_step", "dds_get_loss", "dds_step_count",
            "dds_launches_last_step", "dds_gemm_flops_per_step", "dds_profile", "dds_profile_read",
            "dds_last_error"]
@@ -59,6 +59,8 @@ def _load():
     lib = C.CDLL(LIB_PATH)
     vp, i32p, f32p = C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_float)
     lib.dds_schedule.argtypes = [C.c_int, C.POINTER(C.c_int), C.c_int64, i32p]
+    lib.dds_step_size.argtypes = [C.c_int, C.c_int64, C.c_float]
+    lib.dds_step_size.restype = C.c_float
     lib.dds_arena_bytes.argtypes = [C.POINTER(dds_spec), C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_size_t)]
     lib.dds_create.argtypes = [C.POINTER(dds_spec), C.c_int, C.c_int, C.POINTER(C.c_int), vp, C.c_size_t, C.POINTER(vp)]
     lib.dds_destroy.argtypes = [vp]
@@ -95,6 +97,13 @@ def _delays_arg(delays, K):
         return None
     assert len(delays) == K
     return (C.c_int * K)(*delays)
+
+
+DDS_ETA_CONSTANT, DDS_ETA_PIECEWISE, DDS_ETA_DIMINISHING = 1, 2, 3
+
+
+def dds_step_size(rule: int, t: int, eta0: float) -> float:
+    return float(lib.dds_step_size(rule, t, eta0))
 
 
 def dds_schedule(K: int, delays: Optional[Sequence[int]], t: int) -> np.ndarray:

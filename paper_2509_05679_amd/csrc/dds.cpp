@@ -111,7 +111,8 @@ struct Module {
   float* master = nullptr;    // [copies][n_master]
   float* momentum = nullptr;  // [copies][n_master]
   char* work = nullptr;       // compute-precision copy (bf16 path), [copies][n_master]
-  double* cons_dev = nullptr; // [2 * layers][W] squared distances to the mean (general mixing matrix only)
+  double* cons_dev = nullptr; // [blocks_update][2][W] squared distances to the mean (general mixing matrix only)
+  std::vector<int> map_update_host;  // (layer, block) pairs of weight copy 0
   // error mailbox written by module k0+1, read by this module
   int err_depth = 0;
   size_t err_bytes = 0;
@@ -472,7 +473,6 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
     m.master = (float*)A.take((size_t)m.n_master * 4 * c.copies);
     if (c.mu != 0.f) m.momentum = (float*)A.take((size_t)m.n_master * 4 * c.copies);
     if (c.dt == DT_BF16) m.work = A.take((size_t)m.n_master * es * c.copies);
-    if (c.gossip) m.cons_dev = (double*)A.take(sizeof(double) * 2 * m.layers.size() * c.W);
     for (Node& nd : m.nodes) {
       if (nd.kind != N_CONV) continue;
       ParamLayer& L = m.layers[nd.layer];
@@ -508,6 +508,7 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
       nb_u += (int)((L.n + 1023) / 1024);
       if (L.need_stash) nb_s += L.RS * ((L.Cin + 63) / 64) * ((L.Coutpad + 63) / 64);  // 64 x 64 tiles per tap
     }
+    if (c.gossip) m.cons_dev = (double*)A.take(sizeof(double) * 2 * (nb_u > 0 ? nb_u : 1) * c.W);
     m.blocks_update = nb_u;  // per weight copy; the tables list copy 0 first, then copy 1, ...
     m.blocks_stash = nb_s;
     m.descs_dev = (UpdateDesc*)A.take(sizeof(UpdateDesc) * m.layers.size() * c.copies);
@@ -844,6 +845,7 @@ int upload_tables(dds_ctx& c) {
     if (!descs.empty()) HIP_TRY(hipMemcpy(m.descs_dev, descs.data(), sizeof(UpdateDesc) * descs.size(), hipMemcpyHostToDevice));
     if (!mu.empty()) HIP_TRY(hipMemcpy(m.map_update_dev, mu.data(), sizeof(int) * mu.size(), hipMemcpyHostToDevice));
     if (!ms.empty()) HIP_TRY(hipMemcpy(m.map_stash_dev, ms.data(), sizeof(int) * ms.size(), hipMemcpyHostToDevice));
+    m.map_update_host.assign(mu.begin(), mu.begin() + 2 * m.blocks_update);
   }
   if (c.gossip) HIP_TRY(hipMemcpy(c.P_dev, c.P.data(), sizeof(float) * c.P.size(), hipMemcpyHostToDevice));
   return DDS_OK;
@@ -855,6 +857,16 @@ int upload_tables(dds_ctx& c) {
 extern "C" {
 
 const char* dds_last_error(void) { return g_err.c_str(); }
+
+float dds_step_size(int rule, int64_t t, float eta0) {
+  if (t < 0) return std::nanf("");
+  switch (rule) {
+    case DDS_ETA_CONSTANT: return eta0;
+    case DDS_ETA_PIECEWISE: return t <= 15000 ? eta0 : t <= 30000 ? eta0 / 10.f : t <= 40000 ? eta0 / 100.f : eta0 / 1000.f;
+    case DDS_ETA_DIMINISHING: return eta0 / (float)(t + 1);
+    default: return std::nanf("");
+  }
+}
 
 int dds_schedule(int K, const int* delays, int64_t t, int32_t* out) {
   if (K < 1 || !out || t < 0) return fail(DDS_EINVAL, "dds_schedule: bad arguments");
@@ -1008,16 +1020,21 @@ int dds_consensus_error(dds_ctx* c, double* host_out, void* stream) {
   if (!c->gossip) return DDS_OK;
   hipStream_t s = (hipStream_t)stream;
   double worst = 0.0;
-  std::vector<double> host;
+  std::vector<double> host, sums;
   for (Module& m : c->mods) {
-    if (m.layers.empty()) continue;
-    const size_t n = 2 * m.layers.size() * c->W;
-    launch_consensus(m.descs_dev, (int)m.layers.size(), c->W, m.n_master, m.cons_dev, s);
+    if (m.blocks_update == 0) continue;
+    const size_t n = (size_t)2 * m.blocks_update * c->W;
+    launch_consensus(m.descs_dev, m.map_update_dev, m.blocks_update, c->W, m.n_master, m.cons_dev, s);
     HIP_TRY(hipGetLastError());
     host.resize(n);
     HIP_TRY(hipMemcpyAsync(host.data(), m.cons_dev, n * sizeof(double), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    for (double v : host) worst = v > worst ? v : worst;
+    sums.assign((size_t)2 * m.layers.size() * c->W, 0.0);  // [layer][part][s], blocks added in order
+    for (int b = 0; b < m.blocks_update; ++b) {
+      const int layer = m.map_update_host[2 * b];
+      for (int e = 0; e < 2 * c->W; ++e) sums[(size_t)layer * 2 * c->W + e] += host[(size_t)b * 2 * c->W + e];
+    }
+    for (double v : sums) worst = v > worst ? v : worst;
   }
   *host_out = std::sqrt(worst);
   return DDS_OK;
@@ -1081,10 +1098,9 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
       if (!c->gossip) {
         launch_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->W, step, c->mu, s);
       } else {
-        // u_r = w_r - lr * direction_r for every data-group (its own splits, no averaging), then the mixing step
-        launch_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update * c->W, 1, step, c->mu, s);
-        launch_mix(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->P_dev, c->W, m.n_master, s);
-        ++c->launches;
+        // u_r = w_r - lr * direction_r from every data-group's own splits, then the mixing step, in one kernel
+        launch_gossip_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->P_dev, c->W, m.n_master, step,
+                             c->mu, s);
       }
       launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, (int)((t + 1) % m.R), s);
       c->launches += 2;

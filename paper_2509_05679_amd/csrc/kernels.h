@@ -128,14 +128,15 @@ void launch_softmax_ce(int dt, const float* logits, const int32_t* labels, void*
 // update: g = (1/W) sum over splits, momentum, SGD on the fp32 master, recast into `work`.
 void launch_update(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks, int W,
                    float lr, float mu, hipStream_t s);
-// General mixing matrix (W weight copies, rep_stride elements apart): the masters hold
-// u_r = w_r - lr*direction_r; this writes w_s = sum_r P[s][r] u_r into master and `work`.
-// descs / block_map / total_blocks: the entries of data-group 0. P: device, W x W row-major.
-void launch_mix(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks, const float* P_dev,
-                int W, long long rep_stride, hipStream_t s);
-// out[(2*layer + part) * W + s] = sum_i (w_s[i] - mean_r w_r[i])^2 in fp64; part 0 = weight, 1 = bias.
-void launch_consensus(const UpdateDesc* descs_dev, int nlayers, int W, long long rep_stride, double* out_dev,
-                      hipStream_t s);
+// General mixing matrix (W weight copies, rep_stride elements apart; a descriptor's nsplit = splits per data-group):
+// u_r = w_r - lr*direction_r from data-group r's own splits, then w_s = sum_r P[s][r] u_r into master
+// and `work`. descs / block_map / total_blocks: the entries of data-group 0. P: device, W x W row-major.
+void launch_gossip_update(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks,
+                          const float* P_dev, int W, long long rep_stride, float lr, float mu, hipStream_t s);
+// Squared distances to the data-group mean: out[(2*b + part) * W + s] for workgroup b of the
+// update block map of data-group 0 (1024 elements of one layer each); part 0 = weight, 1 = bias; fp64.
+void launch_consensus(const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks, int W,
+                      long long rep_stride, double* out_dev, hipStream_t s);
 // work <- master
 void launch_recast(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks,
                    hipStream_t s);

@@ -321,61 +321,109 @@ __global__ __launch_bounds__(256) void recast_kernel(const UpdateDesc* descs, co
   }
 }
 
-// Mixing step of Section 3.3 with a general matrix P: the master arrays of the W data-groups
-// hold u_r = w_r - lr * direction_r (left there by update_kernel, one descriptor per data-group);
-// this kernel replaces them by w_s = sum_r P[s][r] * u_r, r ascending, in fp32, and refreshes the
-// compute-precision copies. descs / block_map: data-group 0's entries; data-group r's arrays lie
-// rep_stride elements further per step of r. One thread owns an element in all W copies, so the
-// update is in place.
+// Update (a)/(b) of Section 3.3 with a general mixing matrix P, for all W data-groups at once:
+//   g_r = sum of data-group r's q splits (in order), v_r = mu*v_r + g_r, u_r = w_r - lr*v_r (or lr*g_r),
+//   w_s = sum_r P[s][r] * u_r (r ascending, fp32), written to the fp32 master and the compute-precision copy.
+// descs / block_map: data-group 0's entries (its `partial` points at split 0 of all W*q splits); data-group
+// r's master / momentum / work lie r*rep_stride elements further. One thread owns four consecutive
+// elements in all W copies, so the update is in place. Every layer's arrays are allocated in whole
+// multiples of 64 elements and split rows in multiples of 4, so the four-wide accesses of the last
+// thread of a layer stay inside that layer's padding.
 template <typename T>
-__global__ __launch_bounds__(256) void mix_kernel(const UpdateDesc* descs, const int* block_map, const float* P, int W,
-                                                  long long rep_stride) {
+__global__ __launch_bounds__(256) void gossip_update_kernel(const UpdateDesc* descs, const int* block_map, const float* P,
+                                                            int W, long long rep_stride, float lr, float mu) {
   const UpdateDesc d = descs[block_map[2 * blockIdx.x]];
-  const long long blk0 = (long long)block_map[2 * blockIdx.x + 1] * 1024;
-  for (int it = 0; it < 4; ++it) {
-    const long long i = blk0 + it * 256 + threadIdx.x;
-    if (i >= d.n) return;
-    float u[32];
+  const long long base = (long long)block_map[2 * blockIdx.x + 1] * 1024 + threadIdx.x * 4;
+  if (base >= d.n) return;
+  const int q = d.nsplit;  // splits per data-group of this layer
+  float4 u[32];
 #pragma unroll
-    for (int r = 0; r < 32; ++r) u[r] = r < W ? d.master[(long long)r * rep_stride + i] : 0.f;
-    for (int s = 0; s < W; ++s) {
-      float a = 0.f;
+  for (int r = 0; r < 32; ++r) {
+    if (r >= W) continue;
+    const float* src = d.partial + (size_t)r * q * d.pstride + base;
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int j = 0; j < q; ++j) {
+      const float4 t = *(const float4*)(src + (size_t)j * d.pstride);
+      g.x += t.x; g.y += t.y; g.z += t.z; g.w += t.w;
+    }
+    if (d.momentum) {
+      float4* vp = (float4*)(d.momentum + (long long)r * rep_stride + base);
+      float4 v = *vp;
+      v.x = mu * v.x + g.x; v.y = mu * v.y + g.y; v.z = mu * v.z + g.z; v.w = mu * v.w + g.w;
+      *vp = v;
+      g = v;
+    }
+    const float4 w = *(const float4*)(d.master + (long long)r * rep_stride + base);
+    u[r] = make_float4(w.x - lr * g.x, w.y - lr * g.y, w.z - lr * g.z, w.w - lr * g.w);
+  }
+  for (int s = 0; s < W; ++s) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-      for (int r = 0; r < 32; ++r)
-        if (r < W) a = fmaf(P[s * W + r], u[r], a);
-      d.master[(long long)s * rep_stride + i] = a;
-      if (d.work) {
-        if (sizeof(T) == 2) ((uint16_t*)d.work)[(long long)s * rep_stride + i] = f2bf(a);
-        else ((float*)d.work)[(long long)s * rep_stride + i] = a;
+    for (int r = 0; r < 32; ++r) {
+      if (r >= W) continue;
+      const float c = P[s * W + r];
+      a.x = fmaf(c, u[r].x, a.x); a.y = fmaf(c, u[r].y, a.y); a.z = fmaf(c, u[r].z, a.z); a.w = fmaf(c, u[r].w, a.w);
+    }
+    *(float4*)(d.master + (long long)s * rep_stride + base) = a;
+    if (d.work) {
+      if (sizeof(T) == 2) {
+        uint2 o;
+        o.x = (uint32_t)f2bf(a.x) | ((uint32_t)f2bf(a.y) << 16);
+        o.y = (uint32_t)f2bf(a.z) | ((uint32_t)f2bf(a.w) << 16);
+        *(uint2*)((char*)d.work + ((long long)s * rep_stride + base) * 2) = o;
+      } else {
+        *(float4*)((char*)d.work + ((long long)s * rep_stride + base) * 4) = a;
       }
     }
   }
 }
 
-// Disagreement between data-groups (experiment section): workgroup (tensor, s) accumulates
-// sum_i (w_s[i] - mean_r w_r[i])^2 in fp64 over one parameter tensor (tensor = 2*layer + {0: weight,
-// 1: bias}) and writes it to out[tensor * W + s]; the host takes the square root of the maximum.
-__global__ __launch_bounds__(256) void consensus_kernel(const UpdateDesc* descs, int W, long long rep_stride, double* out) {
-  const UpdateDesc d = descs[blockIdx.x >> 1];
-  const int s = blockIdx.y;
+// Disagreement between data-groups (experiment section). Workgroup b owns 1024 elements of one
+// layer (block_map entry b of data-group 0) and writes, for part 0 (weight) and 1 (bias) and every
+// data-group s, sum_i (w_s[i] - mean_r w_r[i])^2 over its elements of that part, in fp64, to
+// out[(2*b + part) * W + s]. The host adds the blocks of a tensor in order and takes the square
+// root of the maximum.
+__global__ __launch_bounds__(256) void consensus_kernel(const UpdateDesc* descs, const int* block_map, int W,
+                                                        long long rep_stride, double* out) {
+  const UpdateDesc d = descs[block_map[2 * blockIdx.x]];
+  const long long blk0 = (long long)block_map[2 * blockIdx.x + 1] * 1024;
   const long long nw = d.n - d.Cout;
-  const long long lo = (blockIdx.x & 1) ? nw : 0, hi = (blockIdx.x & 1) ? d.n : nw;
-  double acc = 0.0;
-  for (long long i = lo + threadIdx.x; i < hi; i += 256) {
+  double acc[2][32];
+#pragma unroll
+  for (int r = 0; r < 32; ++r) acc[0][r] = acc[1][r] = 0.0;
+  for (int it = 0; it < 4; ++it) {
+    const long long i = blk0 + it * 256 + threadIdx.x;
+    if (i >= d.n) break;
+    float w[32];
     double mean = 0.0;
-    for (int r = 0; r < W; ++r) mean += (double)d.master[(long long)r * rep_stride + i];
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+      if (r < W) { w[r] = d.master[(long long)r * rep_stride + i]; mean += (double)w[r]; }
     mean /= (double)W;
-    const double e = (double)d.master[(long long)s * rep_stride + i] - mean;
-    acc += e * e;
+    const bool is_bias = i >= nw;
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+      if (r < W) {
+        const double e = (double)w[r] - mean;
+        acc[0][r] += is_bias ? 0.0 : e * e;
+        acc[1][r] += is_bias ? e * e : 0.0;
+      }
   }
   __shared__ double red[256];
-  red[threadIdx.x] = acc;
-  __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) out[(size_t)blockIdx.x * W + s] = red[0];
+#pragma unroll
+  for (int part = 0; part < 2; ++part)
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+      if (r >= W) continue;  // uniform
+      red[threadIdx.x] = acc[part][r];
+      __syncthreads();
+      for (int h = 128; h > 0; h >>= 1) {
+        if ((int)threadIdx.x < h) red[threadIdx.x] += red[threadIdx.x + h];
+        __syncthreads();
+      }
+      if (threadIdx.x == 0) out[((size_t)2 * blockIdx.x + part) * W + r] = red[0];
+      __syncthreads();
+    }
 }
 
 // transposed snapshot: stash[slot][c][tap][kpad] <- master[k][tap][cpad], zero for k >= Cout.
@@ -498,15 +546,16 @@ void launch_stash(int dt, const UpdateDesc* descs, const int* block_map, int tot
   DDS_DISPATCH(dt, stash_kernel, <<<total_blocks, 256, 0, s>>>(descs, block_map, slot));
 }
 
-void launch_mix(int dt, const UpdateDesc* descs, const int* block_map, int total_blocks, const float* P, int W,
-                long long rep_stride, hipStream_t s) {
+void launch_gossip_update(int dt, const UpdateDesc* descs, const int* block_map, int total_blocks, const float* P, int W,
+                          long long rep_stride, float lr, float mu, hipStream_t s) {
   if (total_blocks <= 0) return;
-  DDS_DISPATCH(dt, mix_kernel, <<<total_blocks, 256, 0, s>>>(descs, block_map, P, W, rep_stride));
+  DDS_DISPATCH(dt, gossip_update_kernel, <<<total_blocks, 256, 0, s>>>(descs, block_map, P, W, rep_stride, lr, mu));
 }
 
-void launch_consensus(const UpdateDesc* descs, int nlayers, int W, long long rep_stride, double* out, hipStream_t s) {
-  if (nlayers <= 0) return;
-  consensus_kernel<<<dim3(2 * nlayers, W), 256, 0, s>>>(descs, W, rep_stride, out);
+void launch_consensus(const UpdateDesc* descs, const int* block_map, int total_blocks, int W, long long rep_stride,
+                      double* out, hipStream_t s) {
+  if (total_blocks <= 0) return;
+  consensus_kernel<<<total_blocks, 256, 0, s>>>(descs, block_map, W, rep_stride, out);
 }
 
 void launch_param_permute(const float* canon, float* internal, int Cout, int Cin, int RS, int Cinpad, int to_internal,

@@ -133,3 +133,19 @@ def test_no_gpu_means_a_loud_failure_not_a_fallback():
     wl = tiny_mlp()
     with pytest.raises(RuntimeError):
         P.Trainer(P.Spec.from_workload(wl), wl.W)
+
+
+def test_step_size_rules_against_printed_values_and_oracle():
+    gold = os.path.join(ROOT, "tests", "golden", "step_size_strategies.txt")
+    rules = {"constant": P.DDS_ETA_CONSTANT, "piecewise": P.DDS_ETA_PIECEWISE, "diminishing": P.DDS_ETA_DIMINISHING}
+    n = 0
+    for line in open(gold):
+        if not line.strip() or line.startswith("#"):
+            continue
+        rule, t, eta = line.split()
+        got = P.dds_step_size(rules[rule], int(t), 0.1)
+        assert got == pytest.approx(float(eta), rel=1e-6), (rule, t)
+        assert got == pytest.approx(fdg.step_size(rule, int(t), 0.1), rel=1e-6)
+        n += 1
+    assert n >= 14
+    assert np.isnan(P.dds_step_size(99, 0, 0.1)) and np.isnan(P.dds_step_size(P.DDS_ETA_CONSTANT, -1, 0.1))

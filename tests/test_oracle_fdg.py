@@ -1,5 +1,6 @@
 """Pins for the oracle's training recurrence (schedule, stale weights, replica
 mean, reductions to plain SGD, consensus)."""
+import math
 import os
 
 import numpy as np
@@ -323,3 +324,28 @@ def test_average_dynamics_and_consensus_bound_under_sparse_gossip():
     for t in range(5):
         pipe0.step([make_batch(wl, 13, t, s) for s in range(S)])
         assert stacked_delta(pipe0) <= gamma ** (t + 1) * d0 * (1 + 1e-9)
+
+
+# ------------------------------------------------------------------ step sizes
+def _step_size_rows():
+    rows = []
+    for line in open(os.path.join(GOLD, "step_size_strategies.txt")):
+        if line.strip() and not line.startswith("#"):
+            rule, t, eta = line.split()
+            rows.append((rule, int(t), float(eta)))
+    return rows
+
+
+def test_step_size_rules_match_the_printed_values():
+    rows = _step_size_rows()
+    assert len(rows) >= 14
+    for rule, t, eta in rows:
+        assert fdg.step_size(rule, t, 0.1) == pytest.approx(eta, rel=1e-12), (rule, t)
+    # Strategy II never increases; the diminishing rule decreases strictly and is square-summable
+    # but not summable (partial sums grow like log T)
+    etas = [fdg.step_size("piecewise", t) for t in range(0, 50000, 500)]
+    assert all(a >= b for a, b in zip(etas, etas[1:]))
+    dim = [fdg.step_size("diminishing", t) for t in range(2000)]
+    assert all(a > b for a, b in zip(dim, dim[1:]))
+    assert sum(d * d for d in dim) < 0.1 ** 2 * (math.pi ** 2 / 6)
+    assert sum(dim) > 0.1 * math.log(2000)
