@@ -3,6 +3,8 @@
 An op record is a dict with key "op" in
   conv      : cin, cout, k, stride, pad      (2-D convolution + bias)
   linear    : cin, cout                      (dense layer + bias, on [N, cin, 1, 1])
+  bn        : c, eps                         (training-mode batch normalisation per data-group:
+                                              statistics over that group's mini-batch; gamma, beta)
   relu
   maxpool2                                   (2x2 window, stride 2)
   gap                                        (global average pool -> [N, C, 1, 1])
@@ -57,15 +59,22 @@ def _relu():
     return {"op": "relu"}
 
 
-def _block(cin, cout, stride, scale):
+def _bn(c, eps=1e-5):
+    return {"op": "bn", "c": c, "eps": eps}
+
+
+def _block(cin, cout, stride, scale, bn=False):
+    """relu(shortcut(x) + scale * conv2(relu(conv1(x)))); with bn: a batch normalisation after
+    each of the two convolutions (the projection shortcut stays a plain convolution)."""
     sc = None
     if stride != 1 or cin != cout:
         sc = {"cin": cin, "cout": cout, "k": 1, "stride": stride, "pad": 0}
+    norm = [_bn(cout)] if bn else []
     return [
         {"op": "res_begin"},
-        _conv(cin, cout, 3, stride),
+        _conv(cin, cout, 3, stride), *norm,
         _relu(),
-        _conv(cout, cout, 3, 1),
+        _conv(cout, cout, 3, 1), *norm,
         {"op": "res_add", "scale": scale, "shortcut": sc},
         _relu(),
     ]
@@ -102,19 +111,21 @@ def _cnn():
     )
 
 
-def _resnet(name, stem, stages, module_blocks, K, W, B, steps, lr=0.01):
-    """stages: list of (channels, n_blocks); module_blocks: blocks per module (len K)."""
+def _resnet(name, stem, stages, module_blocks, K, W, B, steps, lr=0.01, bn=False):
+    """stages: list of (channels, n_blocks); module_blocks: blocks per module (len K).
+    bn: the standard form (batch normalisation after every main-path convolution, residual
+    branch added unscaled) instead of the normalisation-free one."""
     nblocks = sum(n for _, n in stages)
     assert sum(module_blocks) == nblocks and len(module_blocks) == K
-    scale = 1.0 / math.sqrt(nblocks)
+    scale = 1.0 if bn else 1.0 / math.sqrt(nblocks)
     blocks = []
     cin = stem
     for si, (c, n) in enumerate(stages):
         for bi in range(n):
             stride = 2 if (bi == 0 and si > 0) else 1
-            blocks.append(_block(cin, c, stride, scale))
+            blocks.append(_block(cin, c, stride, scale, bn))
             cin = c
-    ops = [_conv(3, stem), _relu()]
+    ops = [_conv(3, stem), *([_bn(stem)] if bn else []), _relu()]
     bounds = [0]
     it = iter(blocks)
     for k0, nb in enumerate(module_blocks):
@@ -131,9 +142,9 @@ def _resnet(name, stem, stages, module_blocks, K, W, B, steps, lr=0.01):
     )
 
 
-def _resnet18():
-    return _resnet("cfg2_resnet18", 64, [(64, 2), (128, 2), (256, 2), (512, 2)],
-                   [2, 2, 2, 2], K=4, W=4, B=128, steps=16)
+def _resnet18(bn=False):
+    return _resnet("cfg2_resnet18" + ("_bn" if bn else ""), 64, [(64, 2), (128, 2), (256, 2), (512, 2)],
+                   [2, 2, 2, 2], K=4, W=4, B=128, steps=16, bn=bn)
 
 
 def _resnet56():
@@ -148,12 +159,12 @@ def _resnet34w():
                    [2] * 8, K=8, W=8, B=256, steps=24)
 
 
-def _paper_resnet20(S, K):
+def _paper_resnet20(S, K, bn=False):
     """The network and batch of the paper's experiments (Section 5: ResNet-20, mini-batch 194 per
     data-group, S in {1, 4} data-groups, K in {1, 2} modules), BatchNorm-free like cfg2-4, on
     synthetic CIFAR-shaped data. K = 2 cuts after the fifth of the nine blocks."""
-    return _resnet(f"paper_r20_S{S}K{K}", 16, [(16, 3), (32, 3), (64, 3)], [9] if K == 1 else [5, 4],
-                   K=K, W=S, B=194, steps=2 * (K - 1) + 10)
+    return _resnet(f"paper_r20_S{S}K{K}" + ("_bn" if bn else ""), 16, [(16, 3), (32, 3), (64, 3)],
+                   [9] if K == 1 else [5, 4], K=K, W=S, B=194, steps=2 * (K - 1) + 10, bn=bn)
 
 
 _BUILDERS = {
@@ -166,9 +177,14 @@ _BUILDERS = {
     "paper_r20_S1K2": lambda: _paper_resnet20(1, 2),
     "paper_r20_S4K1": lambda: _paper_resnet20(4, 1),
     "paper_r20_S4K2": lambda: _paper_resnet20(4, 2),
+    # the same networks in their standard form, with training-mode batch normalisation
+    "cfg2_resnet18_bn": lambda: _resnet18(bn=True),
+    "paper_r20_S4K2_bn": lambda: _paper_resnet20(4, 2, bn=True),
+    "paper_r20_S1K1_bn": lambda: _paper_resnet20(1, 1, bn=True),
 }
-WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("cfg"))  # the five benchmark configurations
-PAPER_WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("paper_"))
+WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("cfg") and not n.endswith("_bn"))  # the five benchmark configurations
+PAPER_WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("paper_") and not n.endswith("_bn"))
+BN_WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.endswith("_bn"))
 
 
 def workload(name: str, *, B: Optional[int] = None, W: Optional[int] = None,
@@ -193,25 +209,26 @@ def workload(name: str, *, B: Optional[int] = None, W: Optional[int] = None,
     return wl
 
 
-def tiny_resnet(K=2, W=2, B=4, hw=8, c=8, precision="f32", steps=8) -> Workload:
+def tiny_resnet(K=2, W=2, B=4, hw=8, c=8, precision="f32", steps=8, bn=False) -> Workload:
     """A 3-block residual net on hw x hw images (one projection block), small
     enough for finite differences and exhaustive checks."""
     scale = 1.0 / math.sqrt(3)
-    ops = [_conv(3, c), _relu()]
-    ops += _block(c, c, 1, scale)
+    ops = [_conv(3, c), *([_bn(c)] if bn else []), _relu()]
+    ops += _block(c, c, 1, scale, bn)
     cut = len(ops)
-    ops += _block(c, 2 * c, 2, scale)
-    ops += _block(2 * c, 2 * c, 1, scale)
+    ops += _block(c, 2 * c, 2, scale, bn)
+    nb2 = len(ops) - cut
+    ops += _block(2 * c, 2 * c, 1, scale, bn)
     ops += [{"op": "gap"}, _linear(2 * c, 10), {"op": "softmax_ce"}]
     if K == 1:
         bounds = [0, len(ops)]
     elif K == 2:
         bounds = [0, cut, len(ops)]
     elif K == 3:
-        bounds = [0, cut, cut + 6, len(ops)]
+        bounds = [0, cut, cut + nb2, len(ops)]
     else:
         raise ValueError("tiny_resnet supports K in 1..3")
-    return Workload(name=f"tiny_resnet_K{K}", ops=ops, bounds=bounds, K=K, W=W, B=B,
+    return Workload(name=f"tiny_resnet_K{K}" + ("_bn" if bn else ""), ops=ops, bounds=bounds, K=K, W=W, B=B,
                     in_shape=(3, hw, hw), classes=10, precision=precision, lr=0.05,
                     momentum=0.0, steps=steps, extra={"blocks": 3, "res_scale": scale})
 

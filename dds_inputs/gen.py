@@ -26,6 +26,7 @@ def make_batch(wl, seed: int, t: int, s: int) -> Tuple[np.ndarray, np.ndarray]:
 def param_shapes(ops) -> List[Tuple[str, tuple, int]]:
     """Canonical parameter tensors of an op list, in order: (name, shape, fan_in).
     conv: weight [cout,cin,k,k] then bias [cout]; linear: weight [cout,cin] then bias;
+    bn: gamma [c] (fan_in -1) then beta [c] (fan_in -2);
     res_add with a projection shortcut: its conv weight then bias."""
     out = []
     for i, op in enumerate(ops):
@@ -37,6 +38,9 @@ def param_shapes(ops) -> List[Tuple[str, tuple, int]]:
         elif kind == "linear":
             out.append((f"{i}.linear.weight", (op["cout"], op["cin"]), op["cin"]))
             out.append((f"{i}.linear.bias", (op["cout"],), 0))
+        elif kind == "bn":
+            out.append((f"{i}.bn.weight", (op["c"],), -1))
+            out.append((f"{i}.bn.bias", (op["c"],), -2))
         elif kind == "res_add" and op.get("shortcut"):
             sc = op["shortcut"]
             k = sc["k"]
@@ -47,7 +51,8 @@ def param_shapes(ops) -> List[Tuple[str, tuple, int]]:
 
 def make_params(wl, seed: int) -> List[List[np.ndarray]]:
     """Initial weights per module (list over modules of lists of float32 arrays in
-    canonical order). Weights ~ N(0, 2/fan_in), biases zero."""
+    canonical order). Weights ~ N(0, 2/fan_in), biases zero; batch-norm gamma ~ 1 + 0.1 N(0,1),
+    beta ~ 0.1 N(0,1) (away from the usual 1 / 0 so that a swapped or dropped one shows)."""
     mods = []
     for k0 in range(wl.K):
         ops = wl.ops[wl.bounds[k0]:wl.bounds[k0 + 1]]
@@ -58,6 +63,10 @@ def make_params(wl, seed: int) -> List[List[np.ndarray]]:
             else:
                 rng = np.random.Generator(
                     np.random.PCG64(np.random.SeedSequence([seed, _PARAM_STREAM, k0, j])))
+                if fan_in < 0:
+                    base = np.float32(1.0 if fan_in == -1 else 0.0)
+                    tensors.append(base + rng.standard_normal(shape, dtype=np.float32) * np.float32(0.1))
+                    continue
                 std = math.sqrt(2.0 / fan_in)
                 tensors.append((rng.standard_normal(shape, dtype=np.float32) * np.float32(std)))
         mods.append(tensors)

@@ -84,6 +84,34 @@ def relu_bwd(dy, mask):
     return torch.where(mask, dy, torch.zeros_like(dy))
 
 
+def batchnorm_fwd(x, gamma, beta, eps):
+    """Batch normalisation in training mode, the layer that follows every convolution in the
+    standard definition of the ResNet-20 of the experiment section; a layer A_l(h, w_l) of
+    Section 2.1 with w_l = (gamma, beta), evaluated on one data-group's mini-batch:
+      mu[c]  = mean over (n, i, j) of x[n,c,i,j]
+      var[c] = mean over (n, i, j) of (x[n,c,i,j] - mu[c])^2      (biased)
+      xhat   = (x - mu) / sqrt(var + eps),   y = gamma[c] * xhat + beta[c]."""
+    mu = x.mean(dim=(0, 2, 3), keepdim=True)
+    var = ((x - mu) ** 2).mean(dim=(0, 2, 3), keepdim=True)
+    rstd = 1.0 / torch.sqrt(var + eps)
+    xhat = (x - mu) * rstd
+    y = gamma.view(1, -1, 1, 1) * xhat + beta.view(1, -1, 1, 1)
+    return y, (xhat, rstd)
+
+
+def batchnorm_bwd(dy, saved, gamma):
+    """Chain rule through batchnorm_fwd, mu and var included (m = N*H*W values per channel):
+      dbeta = sum dy,  dgamma = sum dy * xhat,
+      dx = gamma / sqrt(var + eps) * (dy - dbeta / m - xhat * dgamma / m)."""
+    xhat, rstd = saved
+    n, c, h, w = dy.shape
+    m = n * h * w
+    dbeta = dy.sum(dim=(0, 2, 3))
+    dgamma = (dy * xhat).sum(dim=(0, 2, 3))
+    dx = gamma.view(1, -1, 1, 1) * rstd * (dy - dbeta.view(1, -1, 1, 1) / m - xhat * dgamma.view(1, -1, 1, 1) / m)
+    return dx, dgamma, dbeta
+
+
 def maxpool2_fwd(x):
     """2x2 windows, stride 2. The selected element of a window is its first
     maximum in row-major order (strict comparisons)."""

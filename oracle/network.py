@@ -1,10 +1,10 @@
 """Forward and backward pass of a contiguous group of layers g(k) = {p_k..q_k}
 (Section 3.2), op by op, fp64.
 
-`ops` is a list of op records (dicts with key "op": conv, linear, relu, maxpool2,
+`ops` is a list of op records (dicts with key "op": conv, linear, bn, relu, maxpool2,
 gap, res_begin, res_add, softmax_ce); `params` is the flat list of that group's
-weight tensors in canonical order (for each conv/linear/projection-shortcut in op
-order: weight, then bias).
+weight tensors in canonical order (for each conv/linear/bn/projection-shortcut in op
+order: weight, then bias; for bn: gamma, then beta).
 """
 from __future__ import annotations
 
@@ -22,7 +22,7 @@ def param_slots(ops) -> List[int]:
     slots, nxt = [], 0
     for op in ops:
         kind = op["op"]
-        has = kind in ("conv", "linear") or (kind == "res_add" and op.get("shortcut"))
+        has = kind in ("conv", "linear", "bn") or (kind == "res_add" and op.get("shortcut"))
         slots.append(nxt if has else -1)
         if has:
             nxt += 2
@@ -47,6 +47,8 @@ def forward(ops, params, x, labels=None):
             h, sv = L.conv2d_fwd(h, params[ps], params[ps + 1], op["stride"], op["pad"])
         elif kind == "linear":
             h, sv = L.linear_fwd(h, params[ps], params[ps + 1])
+        elif kind == "bn":
+            h, sv = L.batchnorm_fwd(h, params[ps], params[ps + 1], op["eps"])
         elif kind == "relu":
             h, sv = L.relu_fwd(h)
         elif kind == "maxpool2":
@@ -94,6 +96,8 @@ def backward(ops, params, saved, dout, need_dx=True):
             d, grads[ps], grads[ps + 1] = L.conv2d_bwd(d, sv, params[ps], op["stride"], op["pad"], want_dx)
         elif kind == "linear":
             d, grads[ps], grads[ps + 1] = L.linear_bwd(d, sv, params[ps], want_dx)
+        elif kind == "bn":
+            d, grads[ps], grads[ps + 1] = L.batchnorm_bwd(d, sv, params[ps])
         elif kind == "relu":
             d = L.relu_bwd(d, sv)
         elif kind == "maxpool2":

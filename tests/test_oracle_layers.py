@@ -163,3 +163,64 @@ def test_softmax_ce_closed_forms():
     # shift invariance incl. large logits (no overflow)
     l4, _ = L.softmax_ce_fwd(z3 + 1000.0, y3)
     assert abs(float(l4) - float(l3)) < 1e-9
+
+
+# ------------------------------------------------------------------ batch normalisation
+def test_batchnorm_forward_statistics_and_library_routine():
+    g = torch.Generator().manual_seed(5)
+    x = 3.0 + 2.0 * torch.randn(5, 6, 4, 3, dtype=DT, generator=g)
+    gamma = 1.0 + 0.3 * torch.randn(6, dtype=DT, generator=g)
+    beta = 0.2 * torch.randn(6, dtype=DT, generator=g)
+    eps = 1e-5
+    y, (xhat, rstd) = L.batchnorm_fwd(x, gamma, beta, eps)
+    ref = F.batch_norm(x, None, None, gamma, beta, training=True, eps=eps)
+    assert torch.allclose(y, ref, rtol=1e-12, atol=1e-12)
+    # written out channel by channel from the definition (biased variance)
+    for c in range(6):
+        vals = x[:, c].reshape(-1)
+        mu = vals.sum() / vals.numel()
+        var = ((vals - mu) ** 2).sum() / vals.numel()
+        expect = gamma[c] * (x[:, c] - mu) / torch.sqrt(var + eps) + beta[c]
+        assert torch.allclose(y[:, c], expect, rtol=1e-12, atol=1e-12)
+        # the output of a channel has mean beta and variance gamma^2 * var / (var + eps)
+        assert abs(float(y[:, c].mean() - beta[c])) < 1e-12
+        assert abs(float(y[:, c].var(unbiased=False) - gamma[c] ** 2 * var / (var + eps))) < 1e-12
+    # invariant under a per-channel shift and (up to eps) scale of the input
+    y2, _ = L.batchnorm_fwd(x + 7.0, gamma, beta, eps)
+    assert torch.allclose(y, y2, rtol=1e-10, atol=1e-10)
+
+
+def test_batchnorm_backward_autograd_finite_differences_and_orthogonality():
+    g = torch.Generator().manual_seed(6)
+    x = torch.randn(4, 3, 2, 5, dtype=DT, generator=g)
+    gamma = 1.0 + 0.3 * torch.randn(3, dtype=DT, generator=g)
+    beta = 0.2 * torch.randn(3, dtype=DT, generator=g)
+    dy = torch.randn(4, 3, 2, 5, dtype=DT, generator=g)
+    eps = 1e-3
+    y, saved = L.batchnorm_fwd(x, gamma, beta, eps)
+    dx, dgamma, dbeta = L.batchnorm_bwd(dy, saved, gamma)
+    xa, ga, ba = (t.clone().requires_grad_() for t in (x, gamma, beta))
+    F.batch_norm(xa, None, None, ga, ba, training=True, eps=eps).backward(dy)
+    assert torch.allclose(dx, xa.grad, rtol=1e-10, atol=1e-12)
+    assert torch.allclose(dgamma, ga.grad, rtol=1e-10, atol=1e-12)
+    assert torch.allclose(dbeta, ba.grad, rtol=1e-10, atol=1e-12)
+    # the input gradient of a channel is orthogonal to the constant, and to xhat up to the eps
+    # term: sum dx*xhat = gamma * rstd * dgamma * eps / (var + eps)
+    xhat, rstd = saved
+    assert torch.allclose(dx.sum(dim=(0, 2, 3)), torch.zeros(3, dtype=DT), atol=1e-12)
+    r = rstd.view(-1)
+    assert torch.allclose((dx * xhat).sum(dim=(0, 2, 3)), gamma * r * dgamma * eps * r * r, rtol=1e-9, atol=1e-12)
+    # central differences of sum(y * dy) with respect to single inputs and parameters
+    h = 1e-6
+    def f(xx, gg, bb):
+        return float((L.batchnorm_fwd(xx, gg, bb, eps)[0] * dy).sum())
+    for idx in [(0, 0, 0, 0), (3, 2, 1, 4), (1, 1, 0, 2)]:
+        xp, xm = x.clone(), x.clone()
+        xp[idx] += h
+        xm[idx] -= h
+        assert abs((f(xp, gamma, beta) - f(xm, gamma, beta)) / (2 * h) - float(dx[idx])) < 1e-6
+    for c in range(3):
+        e = torch.zeros(3, dtype=DT)
+        e[c] = h
+        assert abs((f(x, gamma + e, beta) - f(x, gamma - e, beta)) / (2 * h) - float(dgamma[c])) < 1e-6
+        assert abs((f(x, gamma, beta + e) - f(x, gamma, beta - e)) / (2 * h) - float(dbeta[c])) < 1e-6

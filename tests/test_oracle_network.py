@@ -23,6 +23,8 @@ def _autograd_net(ops, params, x, y):
             h = F.conv2d(h, ps[s], ps[s + 1], stride=op["stride"], padding=op["pad"])
         elif k == "linear":
             h = F.linear(h.flatten(1), ps[s], ps[s + 1]).view(h.shape[0], -1, 1, 1)
+        elif k == "bn":
+            h = F.batch_norm(h, None, None, ps[s], ps[s + 1], training=True, eps=op["eps"])
         elif k == "relu":
             h = F.relu(h)
         elif k == "maxpool2":
@@ -47,7 +49,11 @@ def _flat_params(wl, seed=0):
     return [torch.as_tensor(p, dtype=DT) for m in mods for p in m]
 
 
-@pytest.mark.parametrize("make", [tiny_resnet, tiny_cnn, tiny_mlp])
+def tiny_resnet_bn():
+    return tiny_resnet(bn=True)
+
+
+@pytest.mark.parametrize("make", [tiny_resnet, tiny_cnn, tiny_mlp, tiny_resnet_bn])
 def test_whole_network_gradient_matches_autograd(make):
     wl = make()
     params = _flat_params(wl)
@@ -64,8 +70,9 @@ def test_whole_network_gradient_matches_autograd(make):
         assert torch.allclose(g1, g2, rtol=1e-10, atol=1e-12)
 
 
-def test_whole_network_gradient_matches_finite_differences():
-    wl = tiny_resnet(K=1, B=2, hw=4, c=4)
+@pytest.mark.parametrize("bn", [False, True])
+def test_whole_network_gradient_matches_finite_differences(bn):
+    wl = tiny_resnet(K=1, B=2 + bn, hw=4, c=4, bn=bn)
     params = _flat_params(wl)
     x, y = make_batch(wl, 0, 0, 0)
     x = torch.as_tensor(x, dtype=DT)
