@@ -50,7 +50,12 @@ enum {
   DDS_OP_RES_BEGIN = 6, /* marks the residual block input x */
   DDS_OP_RES_ADD = 7,   /* y = shortcut(x) + res_scale * y_main. cout == 0: identity
                            shortcut; else a conv(cin,cout,ksize,stride,pad)+bias */
-  DDS_OP_SOFTMAX_CE = 8 /* mean softmax cross-entropy; must be the last layer */
+  DDS_OP_SOFTMAX_CE = 8, /* mean softmax cross-entropy; must be the last layer */
+  DDS_OP_BATCHNORM = 9  /* cout = channels, res_scale = eps. Training-mode batch normalisation with
+                           statistics over each data-group's own mini-batch (biased variance); must
+                           directly follow CONV2D or LINEAR, and RES_ADD / RELU may follow it as they
+                           follow a convolution. Parameters: gamma [cout] ("weight") then beta [cout]
+                           ("bias") in the canonical order, at the position of this layer */
 };
 
 enum { DDS_F32 = 0, DDS_BF16_F32MASTER = 1 };
@@ -111,8 +116,9 @@ int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* aren
 int dds_destroy(dds_ctx* ctx);
 
 /* Number of fp32 parameters of a module in canonical order: for every CONV2D /
- * LINEAR / RES_ADD-with-projection in layer order, weight [cout,cin,k,k] (linear:
- * [cout,cin]) then bias [cout]. Negative error code on failure. */
+ * LINEAR / BATCHNORM / RES_ADD-with-projection in layer order, weight [cout,cin,k,k] (linear:
+ * [cout,cin]; batch normalisation: gamma [cout]) then bias [cout] (beta). Negative error code
+ * on failure. */
 int64_t dds_param_count(const dds_ctx* ctx, int module);
 
 /* Copies a module's fp32 master weights to / from dst / src (device-addressable,

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libdds.so")
 DDS_OK, DDS_EINVAL, DDS_ENOMEM, DDS_EHIP, DDS_EUNSUPPORTED = 0, -1, -2, -3, -4
 DDS_SCHED_INTS = 8
 OPS = {"conv": 1, "linear": 2, "relu": 3, "maxpool2": 4, "gap": 5, "res_begin": 6, "res_add": 7,
-       "softmax_ce": 8}
+       "softmax_ce": 8, "bn": 9}
 PRECISION = {"f32": 0, "bf16": 1}
 
 EXPORTS = ["dds_schedule", "dds_step_size", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
@@ -125,6 +125,9 @@ class Spec:
                 L.cin, L.cout, L.ksize, L.stride, L.pad = op["cin"], op["cout"], op["k"], op["stride"], op["pad"]
             elif op["op"] == "linear":
                 L.cin, L.cout, L.ksize, L.stride, L.pad = op["cin"], op["cout"], 1, 1, 0
+            elif op["op"] == "bn":
+                L.cin = L.cout = op["c"]
+                L.res_scale = op["eps"]
             elif op["op"] == "res_add":
                 L.res_scale = op["scale"]
                 sc = op.get("shortcut")

@@ -52,7 +52,7 @@ constexpr int G_ERR_IN = -2;   // mailbox filled by module k0+1 (gradient of thi
 constexpr int G_ERR_OUT = -3;  // mailbox read by module k0-1 (gradient of this module's input)
 
 enum TensorKind { T_RING, T_TEMP, T_EXTERNAL };
-enum NodeKind { N_CONV, N_MAXPOOL, N_GAP, N_CE };
+enum NodeKind { N_CONV, N_MAXPOOL, N_GAP, N_CE, N_BN };
 
 struct Tensor {
   int C = 0, Cpad = 0, H = 0, W = 0;
@@ -90,6 +90,11 @@ struct Node {
   int gout = G_NONE, gin = G_NONE, addend = G_NONE;
   bool mask_in = false;
   bool out_f32 = false;
+  // batch normalisation (N_BN): layer = its gamma / beta block
+  float eps = 0.f;
+  size_t stats_off = 0;    // mean, rstd, gamma of the forwarded mini-batch, inside the ring slot
+  int bn_nsplit = 0;       // row splits per data-group
+  long long bn_rows_per_split = 0;
   int fold_sc = -1;        // first conv of a projection block: node of the 1x1 shortcut whose dgrad rides in this one's
   bool dgrad_folded = false;  // shortcut node: no dgrad launch of its own
 };
@@ -107,6 +112,7 @@ struct Module {
   std::vector<GradBuf> grads;
   size_t slot_bytes = 0;
   char* ring = nullptr;
+  double* bn_scratch = nullptr;  // partial sums of the batch-normalisation forward (largest node of the module)
   long long n_master = 0;  // floats per weight copy
   float* master = nullptr;    // [copies][n_master]
   float* momentum = nullptr;  // [copies][n_master]
@@ -262,8 +268,7 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
         nd.in = cur;
         nd.layer = add_layer(m, L.cin, L.cout, ks, st, pd, dt);
         int nxt = i + 1;
-        bool fuse_res = nxt < hi && sp.layers[nxt].op == DDS_OP_RES_ADD;
-        bool to_ce = nxt < hi && sp.layers[nxt].op == DDS_OP_SOFTMAX_CE;
+        const bool to_ce = nxt < hi && sp.layers[nxt].op == DDS_OP_SOFTMAX_CE;
         const int odt = to_ce ? DT_F32 : dt;
         int out = new_tensor(m, N, L.cout, Ho, Wo, odt, T_RING);
         if (to_ce) {  // logits: fp32 values, padded like a compute-precision tensor so dlogits can mirror it
@@ -273,13 +278,33 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
           nd.out_f32 = true;
         }
         nd.out = out;
+        // A batch normalisation takes over what would otherwise be fused into the convolution's
+        // epilogue: the residual addition (with its scale) and the ReLU.
+        Node bn;
+        const bool have_bn = nxt < hi && sp.layers[nxt].op == DDS_OP_BATCHNORM;
+        if (have_bn) {
+          const dds_layer& Bn = sp.layers[nxt];
+          if (Bn.cout != L.cout) return fail(DDS_EINVAL, "layer %d: BATCHNORM over %d channels after %d", nxt, Bn.cout, L.cout);
+          if (!(Bn.res_scale > 0.f)) return fail(DDS_EINVAL, "layer %d: BATCHNORM needs eps > 0 (in res_scale)", nxt);
+          if (L.cout > 2048) return fail(DDS_EUNSUPPORTED, "layer %d: BATCHNORM over more than 2048 channels", nxt);
+          bn.kind = N_BN;
+          bn.in = out;
+          bn.eps = Bn.res_scale;
+          bn.layer = add_layer(m, 1, L.cout, 1, 1, 0, dt);  // gamma as a [cout][1] weight, beta as its bias
+          bn.out = new_tensor(m, N, L.cout, Ho, Wo, dt, T_RING);
+          ++nxt;
+        }
+        Node& tgt = have_bn ? bn : nd;  // the node whose output the block / the ReLU sees
+        const int tgt_out = have_bn ? bn.out : out;
+        const bool fuse_res = nxt < hi && sp.layers[nxt].op == DDS_OP_RES_ADD;
+        const int res_add_at = nxt;
         Node sc_node;
         bool have_sc = false;
         if (fuse_res) {
           if (res_in < 0) return fail(DDS_EINVAL, "layer %d: RES_ADD without RES_BEGIN", nxt);
           const dds_layer& A = sp.layers[nxt];
           const Tensor tx = m.tensors[res_in];
-          nd.alpha = A.res_scale;
+          tgt.alpha = A.res_scale;
           if (A.cout > 0) {
             if (A.cin != tx.C || A.cout != L.cout) return fail(DDS_EINVAL, "layer %d: shortcut conv shape mismatch", nxt);
             if (A.ksize < 1 || (A.stride != 1 && A.stride != 2) || A.pad < 0 || A.pad >= A.ksize)
@@ -290,34 +315,37 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
             sc_node.in = res_in;
             sc_node.out = new_tensor(m, N, A.cout, Ho, Wo, dt, T_TEMP);
             have_sc = true;
-            nd.res = sc_node.out;
+            tgt.res = sc_node.out;
           } else {
             if (tx.C != L.cout || tx.H != Ho || tx.W != Wo)
               return fail(DDS_EINVAL, "layer %d: identity shortcut needs equal shapes", nxt);
-            nd.res = res_in;
+            tgt.res = res_in;
           }
           ++nxt;
         }
         if (nxt < hi && sp.layers[nxt].op == DDS_OP_RELU) {
-          nd.relu = true;
-          m.tensors[out].relu_out = true;
-          m.tensors[out].has_bits = !nd.out_f32 && m.tensors[out].Cpad % 8 == 0;
+          tgt.relu = true;
+          m.tensors[tgt_out].relu_out = true;
+          m.tensors[tgt_out].has_bits = !tgt.out_f32 && m.tensors[tgt_out].Cpad % 8 == 0;
           ++nxt;
         }
         if (have_sc) {
-          // canonical order: main-path convs first, then the projection (it sits at RES_ADD)
-          const dds_layer& A = sp.layers[i + 1];
+          // canonical order: main-path layers first, then the projection (it sits at RES_ADD)
+          const dds_layer& A = sp.layers[res_add_at];
           sc_node.layer = add_layer(m, A.cin, A.cout, A.ksize, A.stride, A.pad, dt);
-          m.nodes.push_back(sc_node);  // runs before the conv whose epilogue adds it
+          m.nodes.push_back(sc_node);  // runs before the node whose epilogue adds it
         }
         m.nodes.push_back(nd);
+        if (have_bn) m.nodes.push_back(bn);
         if (fuse_res) res_in = -1;
-        cur = out;
+        cur = tgt_out;
         i = nxt - 1;
         break;
       }
       case DDS_OP_RELU:
-        return fail(DDS_EUNSUPPORTED, "layer %d: RELU must directly follow CONV2D, LINEAR or RES_ADD", i);
+        return fail(DDS_EUNSUPPORTED, "layer %d: RELU must directly follow CONV2D, LINEAR, BATCHNORM or RES_ADD", i);
+      case DDS_OP_BATCHNORM:
+        return fail(DDS_EUNSUPPORTED, "layer %d: BATCHNORM must directly follow CONV2D or LINEAR", i);
       case DDS_OP_MAXPOOL2: {
         const Tensor ti = m.tensors[cur];
         if (ti.H % 2 || ti.W % 2) return fail(DDS_EUNSUPPORTED, "layer %d: MAXPOOL2 needs even height and width", i);
@@ -344,7 +372,7 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
         res_in = cur;
         break;
       case DDS_OP_RES_ADD:
-        return fail(DDS_EUNSUPPORTED, "layer %d: RES_ADD must directly follow the block's last CONV2D", i);
+        return fail(DDS_EUNSUPPORTED, "layer %d: RES_ADD must directly follow the block's last CONV2D (or its BATCHNORM)", i);
       case DDS_OP_SOFTMAX_CE: {
         if (k0 != K - 1 || i != sp.n_layers - 1) return fail(DDS_EINVAL, "layer %d: SOFTMAX_CE must be the last layer", i);
         const Tensor ti = m.tensors[cur];
@@ -388,7 +416,7 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
     if (to.kind == T_TEMP) {
       // projection shortcut: find the conv that consumes it
       for (size_t nj = ni + 1; nj < m.nodes.size(); ++nj)
-        if (m.nodes[nj].kind == N_CONV && m.nodes[nj].res == nd.out) { nd.gout = m.tensors[m.nodes[nj].out].grad; break; }
+        if ((m.nodes[nj].kind == N_CONV || m.nodes[nj].kind == N_BN) && m.nodes[nj].res == nd.out) { nd.gout = m.tensors[m.nodes[nj].out].grad; break; }
       if (nd.gin != G_NONE) {  // its input gradient goes to a scratch buffer the block's first conv adds
         GradBuf g;
         g.bytes = m.tensors[nd.in].bytes;
@@ -403,7 +431,7 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
   // residual wiring: the first conv of a block adds the shortcut's gradient
   for (size_t ni = 0; ni < m.nodes.size(); ++ni) {
     Node& nd = m.nodes[ni];
-    if (nd.kind != N_CONV || nd.res < 0) continue;
+    if ((nd.kind != N_CONV && nd.kind != N_BN) || nd.res < 0) continue;
     const Tensor& tr = m.tensors[nd.res];
     int block_in;
     int shortcut_grad;
@@ -465,8 +493,25 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
         off = align_up(off + t.bytes, 256);
         if (t.has_bits) { t.bits_off = off; off = align_up(off + (size_t)c.N * t.H * t.W * t.Cpad / 8, 256); }
       }
+    // batch normalisation: what the backward of a mini-batch needs from its forward (mean, rstd, gamma
+    // per data-group and channel) lives in the ring slot too; the row splits are fixed here
+    size_t bn_scratch_bytes = 0;
+    for (Node& nd : m.nodes) {
+      if (nd.kind != N_BN) continue;
+      const Tensor& tb = m.tensors[nd.out];
+      nd.stats_off = off;
+      off = align_up(off + (size_t)c.W * 3 * tb.Cpad * 4, 256);
+      const long long rows_per_rep = (long long)c.B * tb.H * tb.W;
+      long long ns = rows_per_rep / 512;
+      ns = ns < 1 ? 1 : ns > 256 ? 256 : ns;
+      nd.bn_rows_per_split = (rows_per_rep + ns - 1) / ns;
+      nd.bn_nsplit = (int)((rows_per_rep + nd.bn_rows_per_split - 1) / nd.bn_rows_per_split);
+      const size_t sb = (size_t)c.W * nd.bn_nsplit * tb.Cpad * 2 * sizeof(double);
+      bn_scratch_bytes = sb > bn_scratch_bytes ? sb : bn_scratch_bytes;
+    }
     m.slot_bytes = off;
     m.ring = A.take(m.slot_bytes * m.R);
+    if (bn_scratch_bytes) m.bn_scratch = (double*)A.take(bn_scratch_bytes);
     for (Tensor& t : m.tensors)
       if (t.kind == T_TEMP) t.temp = A.take(t.bytes);
     for (GradBuf& g : m.grads) g.ptr = A.take(g.bytes);
@@ -474,6 +519,12 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
     if (c.mu != 0.f) m.momentum = (float*)A.take((size_t)m.n_master * 4 * c.copies);
     if (c.dt == DT_BF16) m.work = A.take((size_t)m.n_master * es * c.copies);
     for (Node& nd : m.nodes) {
+      if (nd.kind == N_BN) {  // one parameter-gradient row per (data-group, row split)
+        ParamLayer& L = m.layers[nd.layer];
+        L.nsplit = c.W * nd.bn_nsplit;
+        L.partial = (float*)A.take((size_t)L.nsplit * L.pstride * 4);
+        continue;
+      }
       if (nd.kind != N_CONV) continue;
       ParamLayer& L = m.layers[nd.layer];
       const Tensor& to = m.tensors[nd.out];
@@ -670,6 +721,31 @@ struct ProfScope {
   }
 };
 
+// Fields of a batch-normalisation launch that forward and backward share; slot = ring slot of the mini-batch.
+BnParams bn_params(dds_ctx& c, Module& m, const Node& nd, int slot) {
+  const ParamLayer& L = m.layers[nd.layer];
+  const Tensor& to = m.tensors[nd.out];
+  BnParams p{};
+  p.gamma = m.master + L.off;
+  p.beta = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
+  p.rep_stride = c.gossip ? m.n_master : 0;
+  p.gstride = L.Cinpad;
+  p.stats = (float*)(m.ring + (size_t)slot * m.slot_bytes + nd.stats_off);
+  p.scratch = m.bn_scratch;
+  p.partial = L.partial;
+  p.pstride = L.pstride;
+  p.W = c.W;
+  p.C = L.Cout;
+  p.ld = to.Cpad;
+  p.nsplit = nd.bn_nsplit;
+  p.rows_per_rep = (long long)c.B * to.H * to.W;
+  p.rows_per_split = nd.bn_rows_per_split;
+  p.eps = nd.eps;
+  p.alpha = nd.alpha;
+  p.relu = nd.relu;
+  return p;
+}
+
 void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
   const int slot = (int)(t % m.R);
   const int es = dtype_size(c.dt);
@@ -710,6 +786,16 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
           ProfScope ps(c, s, 0, 2.0 * p.M * L.Cout * L.Cin * L.RS);
           ps.cls += 3 * launch_conv(c.dt, p, s);
         }
+        break;
+      }
+      case N_BN: {
+        BnParams p = bn_params(c, m, nd, slot);
+        p.x = x;
+        p.y = y;
+        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
+        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
+        launch_bn_forward(c.dt, p, s);
+        ++c.launches;
         break;
       }
       case N_MAXPOOL:
@@ -796,6 +882,15 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
           }
           ++c.launches;
         }
+        break;
+      }
+      case N_BN: {
+        BnParams p = bn_params(c, m, nd, slot);
+        p.x = x;
+        p.dy = gout;
+        p.dx = gin;
+        launch_bn_backward(c.dt, p, s);
+        c.launches += 2;
         break;
       }
       case N_MAXPOOL:

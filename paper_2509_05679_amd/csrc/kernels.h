@@ -81,6 +81,30 @@ struct WgradParams {
   float alpha;
 };
 
+// Training-mode batch normalisation of a [W * rows_per_rep][ld] tensor, statistics per data-group.
+//   forward : y = relu?( alpha * (gamma * (x - mean) * rstd + beta) + res ), stats <- mean, rstd, gamma
+//   backward: dgamma / dbeta partial rows (one per (data-group, split)), dx from dy, x and the saved stats
+struct BnParams {
+  const void* x;      // input of the normalisation (the convolution output), dtype T
+  void* y;            // forward output, dtype T
+  const void* res;    // added after the normalisation (same layout as y) or null
+  void* bits_out;     // sign plane of y ([row][ld / 8] bytes) or null
+  const void* dy;     // backward: gradient with respect to y (already masked by y > 0 where relu)
+  void* dx;           // backward: gradient with respect to x
+  const float* gamma; // fp32 master: gamma[c * gstride]
+  const float* beta;  // beta[c]
+  long long rep_stride;  // floats between the parameters of consecutive data-groups (0: shared)
+  int gstride;
+  float* stats;       // [W][3][ld]: mean, rstd, gamma of this mini-batch
+  double* scratch;    // forward only: [W][nsplit][ld][2] partial sums
+  float* partial;     // backward: [W * nsplit][pstride] parameter-gradient rows
+  long long pstride;
+  int W, C, ld, nsplit;
+  long long rows_per_rep, rows_per_split;
+  float eps, alpha;
+  int relu;
+};
+
 struct IngestParams {
   const float* x[32];
   const int32_t* y[32];
@@ -143,6 +167,9 @@ void launch_recast(int dt, const UpdateDesc* descs_dev, const int* block_map_dev
 // stash[slot] <- transpose(master); block_map enumerates blocks of Cin*RS*Coutpad elements
 void launch_stash(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks, int slot,
                   hipStream_t s);
+// two kernels each: per-split sums, then the streaming pass
+void launch_bn_forward(int dt, const BnParams& p, hipStream_t s);
+void launch_bn_backward(int dt, const BnParams& p, hipStream_t s);
 // canonical [Cout][Cin][R][S] (+bias) <-> internal [Cout][RS][Cinpad] (+bias)
 void launch_param_permute(const float* canon, float* internal, int Cout, int Cin, int RS, int Cinpad,
                           int to_internal, hipStream_t s);

@@ -84,7 +84,10 @@ def rel_errors(wl, hip_params, orc_params, init=None):
             if init is not None:
                 i0 = init[k0][sl]
                 du = np.linalg.norm(b - i0)
-                upd = (err / du) if du > 0 else (0.0 if err == 0 else np.inf)
+                # "no update yet": the oracle's fp64 mixing sum_r (1/S) w can move a weight by an ulp
+                # of fp64 when 1/S is not a power of two, which is not an update to compare against
+                floor = 1e-13 * max(np.linalg.norm(i0), 1.0)
+                upd = (err / du) if du > floor else (0.0 if err <= floor else np.inf)
             tensor_rows.append((k0, name, rel, upd))
             g = groups.setdefault(name.rsplit(".", 1)[0], [0.0, 0.0])
             g[0] += err ** 2
