@@ -112,7 +112,8 @@ struct Module {
   std::vector<GradBuf> grads;
   size_t slot_bytes = 0;
   char* ring = nullptr;
-  double* bn_scratch = nullptr;  // partial sums of the batch-normalisation forward (largest node of the module)
+  double* bn_scratch = nullptr;  // per-split sums of the batch-normalisation kernels (largest node of the module)
+  double* bn_totals = nullptr;   // dbeta / dgamma per data-group and channel of the node being back-propagated
   long long n_master = 0;  // floats per weight copy
   float* master = nullptr;    // [copies][n_master]
   float* momentum = nullptr;  // [copies][n_master]
@@ -495,23 +496,26 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
       }
     // batch normalisation: what the backward of a mini-batch needs from its forward (mean, rstd, gamma
     // per data-group and channel) lives in the ring slot too; the row splits are fixed here
-    size_t bn_scratch_bytes = 0;
+    size_t bn_scratch_bytes = 0, bn_totals_bytes = 0;
     for (Node& nd : m.nodes) {
       if (nd.kind != N_BN) continue;
       const Tensor& tb = m.tensors[nd.out];
       nd.stats_off = off;
       off = align_up(off + (size_t)c.W * 3 * tb.Cpad * 4, 256);
       const long long rows_per_rep = (long long)c.B * tb.H * tb.W;
-      long long ns = rows_per_rep / 512;
-      ns = ns < 1 ? 1 : ns > 256 ? 256 : ns;
+      // about 32 KiB of the tensor per workgroup, at most 512 splits per data-group
+      long long ns = rows_per_rep * tb.Cpad * es / 32768;
+      ns = ns < 1 ? 1 : ns > 512 ? 512 : ns;
       nd.bn_rows_per_split = (rows_per_rep + ns - 1) / ns;
       nd.bn_nsplit = (int)((rows_per_rep + nd.bn_rows_per_split - 1) / nd.bn_rows_per_split);
       const size_t sb = (size_t)c.W * nd.bn_nsplit * tb.Cpad * 2 * sizeof(double);
+      const size_t tb_bytes = (size_t)c.W * tb.Cpad * 2 * sizeof(double);
       bn_scratch_bytes = sb > bn_scratch_bytes ? sb : bn_scratch_bytes;
+      bn_totals_bytes = tb_bytes > bn_totals_bytes ? tb_bytes : bn_totals_bytes;
     }
     m.slot_bytes = off;
     m.ring = A.take(m.slot_bytes * m.R);
-    if (bn_scratch_bytes) m.bn_scratch = (double*)A.take(bn_scratch_bytes);
+    if (bn_scratch_bytes) { m.bn_scratch = (double*)A.take(bn_scratch_bytes); m.bn_totals = (double*)A.take(bn_totals_bytes); }
     for (Tensor& t : m.tensors)
       if (t.kind == T_TEMP) t.temp = A.take(t.bytes);
     for (GradBuf& g : m.grads) g.ptr = A.take(g.bytes);
@@ -519,9 +523,9 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
     if (c.mu != 0.f) m.momentum = (float*)A.take((size_t)m.n_master * 4 * c.copies);
     if (c.dt == DT_BF16) m.work = A.take((size_t)m.n_master * es * c.copies);
     for (Node& nd : m.nodes) {
-      if (nd.kind == N_BN) {  // one parameter-gradient row per (data-group, row split)
+      if (nd.kind == N_BN) {  // one parameter-gradient row per data-group
         ParamLayer& L = m.layers[nd.layer];
-        L.nsplit = c.W * nd.bn_nsplit;
+        L.nsplit = c.W;
         L.partial = (float*)A.take((size_t)L.nsplit * L.pstride * 4);
         continue;
       }
@@ -732,6 +736,7 @@ BnParams bn_params(dds_ctx& c, Module& m, const Node& nd, int slot) {
   p.gstride = L.Cinpad;
   p.stats = (float*)(m.ring + (size_t)slot * m.slot_bytes + nd.stats_off);
   p.scratch = m.bn_scratch;
+  p.totals = m.bn_totals;
   p.partial = L.partial;
   p.pstride = L.pstride;
   p.W = c.W;

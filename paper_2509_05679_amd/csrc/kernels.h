@@ -96,8 +96,9 @@ struct BnParams {
   long long rep_stride;  // floats between the parameters of consecutive data-groups (0: shared)
   int gstride;
   float* stats;       // [W][3][ld]: mean, rstd, gamma of this mini-batch
-  double* scratch;    // forward only: [W][nsplit][ld][2] partial sums
-  float* partial;     // backward: [W * nsplit][pstride] parameter-gradient rows
+  double* scratch;    // [W][nsplit][ld][2] per-split sums (forward: x, x^2; backward: g, g * xhat)
+  double* totals;     // backward: [W][ld][2] dbeta, dgamma per data-group
+  float* partial;     // backward: [W][pstride] parameter-gradient rows, one per data-group
   long long pstride;
   int W, C, ld, nsplit;
   long long rows_per_rep, rows_per_split;
@@ -167,7 +168,7 @@ void launch_recast(int dt, const UpdateDesc* descs_dev, const int* block_map_dev
 // stash[slot] <- transpose(master); block_map enumerates blocks of Cin*RS*Coutpad elements
 void launch_stash(int dt, const UpdateDesc* descs_dev, const int* block_map_dev, int total_blocks, int slot,
                   hipStream_t s);
-// two kernels each: per-split sums, then the streaming pass
+// three kernels each: per-split sums, their fold per data-group and channel, the streaming pass
 void launch_bn_forward(int dt, const BnParams& p, hipStream_t s);
 void launch_bn_backward(int dt, const BnParams& p, hipStream_t s);
 // canonical [Cout][Cin][R][S] (+bias) <-> internal [Cout][RS][Cinpad] (+bias)

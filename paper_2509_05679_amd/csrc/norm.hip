@@ -91,7 +91,18 @@ __global__ __launch_bounds__(256) void bn_fwd_stats_kernel(BnParams p) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) s[i] = ss[i] = 0.0;
   if (l.active) {
-    for (long long r = l.row_lo + l.tr; r < l.row_hi; r += l.rpp) {
+    // four rows per trip: four independent 16-byte loads in flight per thread
+    long long r = l.row_lo + l.tr;
+    for (; r + 3 * l.rpp < l.row_hi; r += 4 * l.rpp) {
+      float f[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) load8<T>(p.x, (size_t)(r + u * l.rpp) * p.ld + l.c0, l.full, f[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { s[i] += (double)f[u][i]; ss[i] += (double)f[u][i] * (double)f[u][i]; }
+    }
+    for (; r < l.row_hi; r += l.rpp) {
       float f[8];
       load8<T>(p.x, (size_t)r * p.ld + l.c0, l.full, f);
 #pragma unroll
@@ -115,49 +126,75 @@ __global__ __launch_bounds__(256) void bn_fwd_stats_kernel(BnParams p) {
   }
 }
 
-// grid (nsplit, W): same row partition as the statistics kernel. Every thread folds the nsplit
-// partial sums of its 8 channels (in order) into scale / shift, then streams its rows.
+// grid (ceil(ld / 16), W), 256 threads = 16 split lanes x 16 channels: folds the nsplit partial sums of a
+// channel (lane j takes splits j, j+16, ...; the sixteen lanes are combined in a fixed order) once per
+// data-group, so that the streaming kernels read finished per-channel values.
+// Forward (sum x, sum x^2): mean, rstd (and the gamma in use) into `stats`. Backward (sum g, sum g*xhat):
+// dbeta, dgamma totals in fp64 into totals[(rep * ld + c) * 2 + {0, 1}] for the streaming kernel, and in fp32
+// into row `rep` of the parameter-gradient partials (dgamma[c] at c * gstride, dbeta[c] at C * gstride + c: the
+// layout of a 1x1 "convolution" with one input channel, so that the update kernels treat gamma / beta like
+// any other layer with one split per data-group).
+template <bool BWD>
+__global__ __launch_bounds__(256) void bn_finalize_kernel(BnParams p) {
+  const int rep = blockIdx.y, lane4 = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + (threadIdx.x & 15);
+  const bool live = BWD ? c < p.C : c < p.ld;
+  double a = 0.0, b = 0.0;
+  if (live) {
+#pragma unroll 8
+    for (int sp = lane4; sp < p.nsplit; sp += 16) {
+      const double* in = p.scratch + (((size_t)rep * p.nsplit + sp) * p.ld + c) * 2;
+      a += in[0];
+      b += in[1];
+    }
+  }
+  __shared__ double red[2][16][16];
+  red[0][lane4][threadIdx.x & 15] = a;
+  red[1][lane4][threadIdx.x & 15] = b;
+  __syncthreads();
+  if (lane4 != 0 || !live) return;
+  const int ch = threadIdx.x & 15;
+  a = b = 0.0;
+  for (int j = 0; j < 16; ++j) { a += red[0][j][ch]; b += red[1][j][ch]; }
+  if (BWD) {
+    double* out = p.totals + ((size_t)rep * p.ld + c) * 2;
+    out[0] = a;  // dbeta
+    out[1] = b;  // dgamma
+    float* row = p.partial + (size_t)rep * p.pstride;
+    row[(size_t)c * p.gstride] = (float)b;
+    row[(size_t)p.C * p.gstride + c] = (float)a;
+  } else {
+    const double m = (double)p.rows_per_rep;
+    const double mean = a / m;
+    double var = b / m - mean * mean;
+    var = var > 0.0 ? var : 0.0;
+    float* st = p.stats + (size_t)rep * 3 * p.ld;
+    st[c] = (float)mean;
+    st[p.ld + c] = (float)(1.0 / sqrt(var + (double)p.eps));
+    st[2 * p.ld + c] = c < p.C ? p.gamma[(size_t)rep * p.rep_stride + (size_t)c * p.gstride] : 0.f;
+  }
+}
+
+// grid (nsplit, W): same row partition as the statistics kernel; streams its rows.
 template <typename T>
 __global__ __launch_bounds__(256) void bn_fwd_apply_kernel(BnParams p) {
   const Lane l = make_lane(p);
   if (!l.active) return;
-  const int rep = blockIdx.y, nsplit = gridDim.x;
-  const float* gamma = p.gamma + (size_t)rep * p.rep_stride;
+  const int rep = blockIdx.y;
   const float* beta = p.beta + (size_t)rep * p.rep_stride;
+  const float* st = p.stats + (size_t)rep * 3 * p.ld;
   float scale[8], shift[8];
-  const double m = (double)p.rows_per_rep;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     scale[i] = shift[i] = 0.f;
     const int c = l.c0 + i;
-    if (c >= p.ld) continue;
-    double a = 0.0, b = 0.0;
-    for (int sp = 0; sp < nsplit; ++sp) {
-      const double* in = p.scratch + (((size_t)rep * nsplit + sp) * p.ld + c) * 2;
-      a += in[0];
-      b += in[1];
-    }
-    const double mean = a / m;
-    double var = b / m - mean * mean;
-    var = var > 0.0 ? var : 0.0;
-    const float rstd = (float)(1.0 / sqrt(var + (double)p.eps));
-    const float g = c < p.C ? gamma[(size_t)c * p.gstride] : 0.f;
-    const float bt = c < p.C ? beta[c] : 0.f;
+    if (c >= p.C) continue;
+    const float mean = st[c], rstd = st[p.ld + c], g = st[2 * p.ld + c];
     scale[i] = p.alpha * g * rstd;
-    shift[i] = p.alpha * (bt - (float)mean * g * rstd);
-    if (blockIdx.x == 0 && l.tr == 0) {  // what the backward of this mini-batch needs
-      float* st = p.stats + (size_t)rep * 3 * p.ld;
-      st[c] = (float)mean;
-      st[p.ld + c] = rstd;
-      st[2 * p.ld + c] = g;
-    }
+    shift[i] = p.alpha * (beta[c] - mean * g * rstd);
   }
-  for (long long r = l.row_lo + l.tr; r < l.row_hi; r += l.rpp) {
+  auto finish_row = [&](long long r, float (&f)[8], const float (&q)[8]) {
     const size_t e = (size_t)r * p.ld + l.c0;
-    float f[8], q[8];
-    load8<T>(p.x, e, l.full, f);
-    if (p.res) load8<T>(p.res, e, l.full, q);
-    uint32_t bits = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       float v = fmaf(f[i], scale[i], shift[i]);
@@ -168,6 +205,7 @@ __global__ __launch_bounds__(256) void bn_fwd_apply_kernel(BnParams p) {
     store8<T>(p.y, e, l.full, f);
     if (p.bits_out) {
       // the sign of the stored (rounded) value, as the convolution epilogues define the plane
+      uint32_t bits = 0;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float stored = sizeof(T) == 2 ? bf2f(f2bf(f[i])) : f[i];
@@ -175,13 +213,32 @@ __global__ __launch_bounds__(256) void bn_fwd_apply_kernel(BnParams p) {
       }
       ((uint8_t*)p.bits_out)[(size_t)r * (p.ld / 8) + l.tg] = (uint8_t)bits;
     }
+  };
+  // four rows per trip: all loads of the trip are issued before the first row is finished
+  long long r = l.row_lo + l.tr;
+  for (; r + 3 * l.rpp < l.row_hi; r += 4 * l.rpp) {
+    float f[4][8], q[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t e = (size_t)(r + u * l.rpp) * p.ld + l.c0;
+      load8<T>(p.x, e, l.full, f[u]);
+      if (p.res) load8<T>(p.res, e, l.full, q[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) finish_row(r + u * l.rpp, f[u], q[u]);
+  }
+  for (; r < l.row_hi; r += l.rpp) {
+    float f[8], q[8];
+    const size_t e = (size_t)r * p.ld + l.c0;
+    load8<T>(p.x, e, l.full, f);
+    if (p.res) load8<T>(p.res, e, l.full, q);
+    finish_row(r, f, q);
   }
 }
 
 // ------------------------------------------------------------------ backward
-// grid (nsplit, W). Writes split row (rep * nsplit + split) of the parameter-gradient partials:
-// dgamma[c] at c * gstride, dbeta[c] at C * gstride + c (the layout of a 1x1 "convolution" with one
-// input channel, so that the update kernels treat gamma / beta like any other layer).
+// grid (nsplit, W). scratch[((rep * nsplit + split) * ld + c) * 2 + {0, 1}] = sum g, sum g * xhat over the split's
+// rows, g = alpha * dy.
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_stats_kernel(BnParams p) {
   const Lane l = make_lane(p);
@@ -199,7 +256,25 @@ __global__ __launch_bounds__(256) void bn_bwd_stats_kernel(BnParams p) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) s[i] = ss[i] = 0.0;
   if (l.active) {
-    for (long long r = l.row_lo + l.tr; r < l.row_hi; r += l.rpp) {
+    long long r = l.row_lo + l.tr;
+    for (; r + 3 * l.rpp < l.row_hi; r += 4 * l.rpp) {
+      float f[4][8], g[4][8];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const size_t e = (size_t)(r + u * l.rpp) * p.ld + l.c0;
+        load8<T>(p.x, e, l.full, f[u]);
+        load8<T>(p.dy, e, l.full, g[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float xh = (f[u][i] - mean[i]) * rstd[i];
+          s[i] += (double)g[u][i];
+          ss[i] += (double)g[u][i] * (double)xh;
+        }
+    }
+    for (; r < l.row_hi; r += l.rpp) {
       const size_t e = (size_t)r * p.ld + l.c0;
       float f[8], g[8];
       load8<T>(p.x, e, l.full, f);
@@ -217,25 +292,24 @@ __global__ __launch_bounds__(256) void bn_bwd_stats_kernel(BnParams p) {
   for (int i = 0; i < 8; ++i) { red[i * 256 + threadIdx.x] = s[i]; red[(8 + i) * 256 + threadIdx.x] = ss[i]; }
   __syncthreads();
   if (l.active && l.tr == 0) {
-    float* out = p.partial + ((size_t)rep * gridDim.x + blockIdx.x) * p.pstride;
+    double* out = p.scratch + (((size_t)rep * gridDim.x + blockIdx.x) * p.ld + l.c0) * 2;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int c = l.c0 + i;
-      if (c >= p.C) break;
+      if (l.c0 + i >= p.ld) break;
       double a = 0.0, b = 0.0;
       for (int t = 0; t < l.rpp; ++t) { a += red[i * 256 + t * cg + l.tg]; b += red[(8 + i) * 256 + t * cg + l.tg]; }
-      out[(size_t)c * p.gstride] = p.alpha * (float)b;            // dgamma
-      out[(size_t)p.C * p.gstride + c] = p.alpha * (float)a;      // dbeta
+      out[2 * i] = (double)p.alpha * a;
+      out[2 * i + 1] = (double)p.alpha * b;
     }
   }
 }
 
-// grid (nsplit, W): folds the group's split rows (in order) into dbeta, dgamma and streams dx.
+// grid (nsplit, W): streams dx from dy, x, the saved statistics and the finished dgamma / dbeta totals.
 template <typename T>
 __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(BnParams p) {
   const Lane l = make_lane(p);
   if (!l.active) return;
-  const int rep = blockIdx.y, nsplit = gridDim.x;
+  const int rep = blockIdx.y;
   const float* st = p.stats + (size_t)rep * 3 * p.ld;
   float mean[8], rstd[8], k0[8], k1[8], k2[8];
   const double m = (double)p.rows_per_rep;
@@ -244,12 +318,8 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(BnParams p) {
     const int c = l.c0 + i;
     mean[i] = rstd[i] = k0[i] = k1[i] = k2[i] = 0.f;
     if (c >= p.C) continue;
-    double db = 0.0, dg = 0.0;
-    for (int sp = 0; sp < nsplit; ++sp) {
-      const float* in = p.partial + ((size_t)rep * nsplit + sp) * p.pstride;
-      dg += (double)in[(size_t)c * p.gstride];
-      db += (double)in[(size_t)p.C * p.gstride + c];
-    }
+    const double* tot = p.totals + ((size_t)rep * p.ld + c) * 2;
+    const double db = tot[0], dg = tot[1];
     mean[i] = st[c];
     rstd[i] = st[p.ld + c];
     const float gr = st[2 * p.ld + c] * rstd[i];  // gamma * rstd
@@ -258,17 +328,32 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(BnParams p) {
     k1[i] = gr * (float)(db / m);
     k2[i] = gr * (float)(dg / m);
   }
-  for (long long r = l.row_lo + l.tr; r < l.row_hi; r += l.rpp) {
-    const size_t e = (size_t)r * p.ld + l.c0;
-    float f[8], g[8];
-    load8<T>(p.x, e, l.full, f);
-    load8<T>(p.dy, e, l.full, g);
+  auto finish_row = [&](long long r, float (&f)[8], const float (&g)[8]) {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float xh = (f[i] - mean[i]) * rstd[i];
       f[i] = k0[i] * g[i] - k1[i] - xh * k2[i];
     }
-    store8<T>(p.dx, e, l.full, f);
+    store8<T>(p.dx, (size_t)r * p.ld + l.c0, l.full, f);
+  };
+  long long r = l.row_lo + l.tr;
+  for (; r + 3 * l.rpp < l.row_hi; r += 4 * l.rpp) {
+    float f[4][8], g[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t e = (size_t)(r + u * l.rpp) * p.ld + l.c0;
+      load8<T>(p.x, e, l.full, f[u]);
+      load8<T>(p.dy, e, l.full, g[u]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) finish_row(r + u * l.rpp, f[u], g[u]);
+  }
+  for (; r < l.row_hi; r += l.rpp) {
+    float f[8], g[8];
+    const size_t e = (size_t)r * p.ld + l.c0;
+    load8<T>(p.x, e, l.full, f);
+    load8<T>(p.dy, e, l.full, g);
+    finish_row(r, f, g);
   }
 }
 
@@ -282,14 +367,18 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_kernel(BnParams p) {
 
 void launch_bn_forward(int dt, const BnParams& p, hipStream_t s) {
   dim3 grid(p.nsplit, p.W);
+  dim3 fgrid((p.ld + 15) / 16, p.W);
   DDS_BN_DISPATCH(dt, bn_fwd_stats_kernel, <<<grid, 256, 0, s>>>(p));
+  bn_finalize_kernel<false><<<fgrid, 256, 0, s>>>(p);
   DDS_BN_DISPATCH(dt, bn_fwd_apply_kernel, <<<grid, 256, 0, s>>>(p));
 }
 
 void launch_bn_backward(int dt, const BnParams& p, hipStream_t s) {
   dim3 grid(p.nsplit, p.W);
+  dim3 fgrid((p.ld + 15) / 16, p.W);
   DDS_BN_DISPATCH(dt, bn_bwd_stats_kernel, <<<grid, 256, 0, s>>>(p));
-  if (p.dx) DDS_BN_DISPATCH(dt, bn_bwd_apply_kernel, <<<grid, 256, 0, s>>>(p));
+  bn_finalize_kernel<true><<<fgrid, 256, 0, s>>>(p);
+  DDS_BN_DISPATCH(dt, bn_bwd_apply_kernel, <<<grid, 256, 0, s>>>(p));
 }
 
 }  // namespace dds
