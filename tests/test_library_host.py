@@ -149,3 +149,23 @@ def test_step_size_rules_against_printed_values_and_oracle():
         n += 1
     assert n >= 14
     assert np.isnan(P.dds_step_size(99, 0, 0.1)) and np.isnan(P.dds_step_size(P.DDS_ETA_CONSTANT, -1, 0.1))
+
+
+def test_batchnorm_spec_validation_and_arena():
+    from dds_inputs.configs import BN_WORKLOAD_NAMES
+    for name in BN_WORKLOAD_NAMES:
+        wl = workload(name)
+        plain = workload(name[:-3])
+        with_bn = P.dds_arena_bytes(P.Spec.from_workload(wl), wl.K, wl.W)
+        assert with_bn > P.dds_arena_bytes(P.Spec.from_workload(plain), plain.K, plain.W)
+    conv = dict(op="conv", cin=3, cout=8, k=3, stride=1, pad=1)
+    tail = [dict(op="gap"), dict(op="linear", cin=8, cout=10), dict(op="softmax_ce")]
+    ok = [conv, dict(op="bn", c=8, eps=1e-5), dict(op="relu")] + tail
+    P.dds_arena_bytes(_spec(ok, [0, len(ok)]), 1, 2)
+    # wrong channel count, eps missing, normalisation not behind a convolution
+    for bad, code in (([conv, dict(op="bn", c=4, eps=1e-5), dict(op="relu")] + tail, P.DDS_EINVAL),
+                      ([conv, dict(op="bn", c=8, eps=0.0), dict(op="relu")] + tail, P.DDS_EINVAL),
+                      ([conv, dict(op="relu"), dict(op="bn", c=8, eps=1e-5)] + tail, P.DDS_EUNSUPPORTED)):
+        with pytest.raises(P.DdsError) as e:
+            P.dds_arena_bytes(_spec(bad, [0, len(bad)]), 1, 2)
+        assert e.value.code == code
