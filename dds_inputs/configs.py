@@ -179,8 +179,10 @@ _BUILDERS = {
     "paper_r20_S4K2": lambda: _paper_resnet20(4, 2),
     # the same networks in their standard form, with training-mode batch normalisation
     "cfg2_resnet18_bn": lambda: _resnet18(bn=True),
-    "paper_r20_S4K2_bn": lambda: _paper_resnet20(4, 2, bn=True),
     "paper_r20_S1K1_bn": lambda: _paper_resnet20(1, 1, bn=True),
+    "paper_r20_S1K2_bn": lambda: _paper_resnet20(1, 2, bn=True),
+    "paper_r20_S4K1_bn": lambda: _paper_resnet20(4, 1, bn=True),
+    "paper_r20_S4K2_bn": lambda: _paper_resnet20(4, 2, bn=True),
 }
 WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("cfg") and not n.endswith("_bn"))  # the five benchmark configurations
 PAPER_WORKLOAD_NAMES = tuple(n for n in _BUILDERS if n.startswith("paper_") and not n.endswith("_bn"))
