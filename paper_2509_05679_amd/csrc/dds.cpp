@@ -842,6 +842,7 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
         w.NK = L.RS * L.Cinpad;
         w.P = c.N * to.H * to.W;
         w.nsplit = L.nsplit;
+        w.nrep = c.W;
         w.pix_per_split = w.P / L.nsplit;
         w.Pl = L.pstride;
         w.alpha = nd.alpha;

@@ -1215,8 +1215,12 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
   const int sub = S2 ? wg.sub[blockIdx.y / wg.cblocks] : 0;
   const int sdy = sub >> 1, sdx = sub & 1;
   const int c0 = (S2 ? blockIdx.y % wg.cblocks : blockIdx.y) * 64;
-  const int tile0 = z * (p.pix_per_split >> 7);
-  const int ntiles = p.pix_per_split >> 7;
+  // Split z = (data-group, j): the data-group's tiles are dealt to its q splits as evenly as whole
+  // tiles allow (tile counts differ by at most one), so a split never mixes two data-groups.
+  const int q = p.nsplit / p.nrep, rep_tiles = (p.P >> 7) / p.nrep;
+  const int zr = z / q, zj = z - zr * q;
+  const int tile0 = zr * rep_tiles + (zj * rep_tiles) / q;
+  const int ntiles = zr * rep_tiles + ((zj + 1) * rep_tiles) / q - tile0;
   const size_t ybytes = (size_t)p.ldy * 2, xbytes = (size_t)p.Cx * 2;
 
   // A tile is 128 consecutive pixels of the flattened (image, row, column) index of the output
@@ -1474,7 +1478,9 @@ bool wgrad_dma_eligible(const WgradParams& p, int* nsub_out, int* cblocks_out, i
   const bool s2 = p.stride == 2 && p.R == p.S && ((p.R == 3 && p.pad == 1) || (p.R == 1 && p.pad == 0)) &&
                   p.H == 2 * p.Ho && p.W == 2 * p.Wo;
   if (!s1 && !s2) return false;
-  if (p.Cx % 64 != 0 || p.zeros == nullptr || p.pix_per_split % 128 != 0 || p.P % 128 != 0) return false;
+  // every data-group's pixels are whole 128-pixel tiles, and no split is empty
+  if (p.nrep < 1 || p.nsplit % p.nrep != 0 || p.P % (128 * p.nrep) != 0 || p.nsplit > p.P / 128) return false;
+  if (p.Cx % 64 != 0 || p.zeros == nullptr) return false;
   // byte offsets of patch rows relative to the tile origin are 32-bit
   if ((long long)(128 + 2 * p.W + 4) * 4 * p.Cx * 2 >= (1ll << 31) || p.Cx * 2 + 256 > kZeroBytes) return false;
   const int lw = ilog2_exact(p.Wo), lh = ilog2_exact(p.Ho);
@@ -1559,17 +1565,17 @@ int wgrad_choose_split(int dt, const WgradParams& shape, int W) {
     // measured on the ResNet-18 step 256 workgroups beat 512 and 1024 (2.95 / 3.13 / 3.45 ms).
     WgradParams probe = shape;
     probe.nsplit = W;
-    probe.pix_per_split = 128;
+    probe.nrep = W;
     int nsub = 0, cblocks = 0;
     if (wgrad_dma_eligible(probe, &nsub, &cblocks)) {
       const int blocks = cdiv(Mout, 64) * nsub * cblocks;
-      int best = 0;
-      for (int q = 1; q * W <= 256; ++q) {
-        if (per_replica % q != 0 || (per_replica / q) % 128 != 0) continue;
-        best = q;
-        if (blocks * W * q >= 256) break;
-      }
-      if (best > 0) return W * best;
+      const int rep_tiles = per_replica / 128;
+      int q = cdiv(256, blocks * W);
+      if (q > rep_tiles) q = rep_tiles;
+      if (q * W > 256) q = 256 / W;
+      if (q < 1) q = 1;
+      probe.nsplit = W * q;
+      if (wgrad_dma_eligible(probe, &nsub, &cblocks)) return W * q;  // the launch will take the same decision
     }
   }
   const int ce = dtype_ce(dt);

@@ -75,8 +75,11 @@ struct WgradParams {
   int R, S, stride, pad;
   int NK;           // R*S*Cx
   int P;            // Nimg*Ho*Wo
-  int pix_per_split;
+  int pix_per_split; // generic kernel: pixels per split (P / nsplit, splits are equal)
   int nsplit;
+  int nrep;          // data-groups: equal runs of consecutive images; nsplit is a multiple of it and no split
+                     // holds pixels of two data-groups (the asynchronous kernel deals each group's 128-pixel
+                     // tiles to its nsplit / nrep splits as evenly as whole tiles allow)
   long long Pl;     // floats between consecutive splits (>= Mout*NK + Mout)
   float alpha;
 };
