@@ -1232,6 +1232,7 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
   const char* zsrc = (const char*)zeros + c16;
   constexpr int pw_total = PROW >> 3;
   const bool ycol_ok = k0 + (c16 >> 1) < p.ldy;   // this lane's 8 output channels exist
+  const bool xcol_ok = c0 + (c16 >> 1) < p.Cx;    // ... and its 8 input channels (tensors narrower than a 64-channel block)
   const size_t tile_ybytes = 128 * ybytes, tile_xbytes = (S2 ? 4 : 1) * 128 * xbytes;
   const char* ysrc0 = (const char*)p.dy + ((size_t)tile0 * 128 + (size_t)(wave * 8 + l8)) * ybytes + (size_t)k0 * 2 + c16;
   const char* xsrc0 = (const char*)p.x + (size_t)tile0 * tile_xbytes + (size_t)c0 * 2 + c16;
@@ -1269,7 +1270,7 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
       const int wl = wave + NWV * u;
       const bool live = live_t && wl < pw_total;
       const int gh = h0 + (pflag[u] & 255) - 1;
-      const bool ok = live && (pflag[u] >> 8) && (unsigned)gh < (unsigned)p.Ho;
+      const bool ok = live && xcol_ok && (pflag[u] >> 8) && (unsigned)gh < (unsigned)p.Ho;
       dma16(ok ? xsrc + prel[u] : zsrc, live ? base + 16384 + wl * 1024 : lds_dump);
     }
   };
@@ -1480,7 +1481,7 @@ bool wgrad_dma_eligible(const WgradParams& p, int* nsub_out, int* cblocks_out, i
   if (!s1 && !s2) return false;
   // every data-group's pixels are whole 128-pixel tiles, and no split is empty
   if (p.nrep < 1 || p.nsplit % p.nrep != 0 || p.P % (128 * p.nrep) != 0 || p.nsplit > p.P / 128) return false;
-  if (p.Cx % 64 != 0 || p.zeros == nullptr) return false;
+  if (p.Cx % 8 != 0 || (p.Cx > 64 && p.Cx % 64 != 0) || p.zeros == nullptr) return false;
   // byte offsets of patch rows relative to the tile origin are 32-bit
   if ((long long)(128 + 2 * p.W + 4) * 4 * p.Cx * 2 >= (1ll << 31) || p.Cx * 2 + 256 > kZeroBytes) return false;
   const int lw = ilog2_exact(p.Wo), lh = ilog2_exact(p.Ho);
@@ -1490,7 +1491,7 @@ bool wgrad_dma_eligible(const WgradParams& p, int* nsub_out, int* cblocks_out, i
   else { th_log = lh; tiles_h = 1; }
   if (!((lw == 5 && th_log == 2) || (lw == 4 && th_log == 3) || (lw == 3 && th_log == 3) || (lw == 2 && th_log == 2))) return false;
   *nsub_out = s2 && p.R == 3 ? 4 : 1;
-  *cblocks_out = p.Cx / 64;
+  *cblocks_out = cdiv(p.Cx, 64);
   if (lw_out) *lw_out = lw;
   if (th_log_out) *th_log_out = th_log;
   if (tiles_h_out) *tiles_h_out = tiles_h;
@@ -1503,7 +1504,7 @@ bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
   const bool s2 = p.stride == 2;
   WgradGeom wg{};
   wg.tiles_h = tiles_h;
-  wg.cblocks = p.Cx / 64;
+  wg.cblocks = cblocks;
   int nsub = 1;
   if (s2) {
     // real tap for (virtual tap, sub-pixel offset): 3x3 pad 1: rows 2oy-1, 2oy, 2oy+1; 1x1 pad 0: row 2oy
