@@ -326,9 +326,11 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p_, int ti
   constexpr int CPR = BKB / 16;   // chunks per tile row
   constexpr int LDK = BKB + 16;
   constexpr int ROWS = 256 / CPR; // rows covered by one pass of all threads
-  constexpr int AP = BM / ROWS, BP = BN / ROWS;
+  // loader passes over the A and B tiles; a B tile of fewer rows than one pass (BN < ROWS) leaves the
+  // threads past its last row idle (their loads read row 0 and are not stored)
+  constexpr int AP = BM / ROWS, BP = BN >= ROWS ? BN / ROWS : 1;
   static_assert((BM / WM) * (BN / WN) == 4, "four waves");
-  static_assert(AP >= 1 && BP >= 1, "tile too small for the loader");
+  static_assert(AP >= 1, "tile too small for the loader");
   __shared__ __align__(16) char smem[2 * (BM + BN) * LDK];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -387,7 +389,7 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p_, int ti
   for (int i = 0; i < BP; ++i) {
     int n = n0 + rbase + i * ROWS;
     b_n[i] = n;
-    b_ok[i] = n < p.Nout;
+    b_ok[i] = n < p.Nout && rbase + i * ROWS < BN;
     b_base[i] = (const char*)p.w + (size_t)(b_ok[i] ? n : 0) * p.Ktot * ES;
   }
   // position of this thread's chunk in (tap, channel) space
@@ -451,7 +453,8 @@ __global__ __launch_bounds__(256, 2) void conv_gemm_kernel(ConvParams p_, int ti
 #pragma unroll
     for (int i = 0; i < AP; ++i) *(uint4*)(As + (rbase + i * ROWS) * LDK + chunk * 16) = keep_if(oka[i], ra[i]);
 #pragma unroll
-    for (int i = 0; i < BP; ++i) *(uint4*)(Bs + (rbase + i * ROWS) * LDK + chunk * 16) = keep_if(okb[i], rb[i]);
+    for (int i = 0; i < BP; ++i)
+      if (BN >= ROWS || rbase + i * ROWS < BN) *(uint4*)(Bs + (rbase + i * ROWS) * LDK + chunk * 16) = keep_if(okb[i], rb[i]);
   };
 
   f32x16_t acc[WN / 32][WM / 32];
@@ -1440,7 +1443,11 @@ int launch_conv_one(const ConvParams& p, hipStream_t s) {
   const bool s2 = p.dgrad && p.stride == 2 && p.Cx % (BKB / (int)sizeof(T)) == 0 &&
                   (p.x2 == nullptr || p.Cx2 % (BKB / (int)sizeof(T)) == 0);
   const int mc = p.Nimg * ((p.Ho + 1) / 2) * ((p.Wo + 1) / 2);
-  if (p.ldy <= 64) {
+  if (p.ldy <= 32 && !s2) {  // narrow layers (16 / 32 output channels): half the padded columns
+    dim3 grid(cdiv(p.M, 256), 1);
+    if (p.dgrad) conv_gemm_kernel<T, 256, 32, 64, 32, BKB, true><<<grid, 256, 0, s>>>(p, 0);
+    else conv_gemm_kernel<T, 256, 32, 64, 32, BKB, false><<<grid, 256, 0, s>>>(p, 0);
+  } else if (p.ldy <= 64) {
     const int tpc = cdiv(mc, 256);
     dim3 grid(s2 ? 4 * tpc : cdiv(p.M, 256), cdiv(p.ldy, 64));
     if (s2) conv_gemm_kernel<T, 256, 64, 64, 64, BKB, true, true><<<grid, 256, 0, s>>>(p, tpc);
