@@ -81,6 +81,21 @@ __device__ __forceinline__ Lane make_lane(const BnParams& p) {
   return l;
 }
 
+// Second half of the workgroup reduction. red[v * 256 + thread] holds quantity v (0-7: first sum of the
+// thread's eight channels, 8-15: second sum) of every thread; thread = row-thread t * cg + channel group g.
+// One thread per (v, g) adds the rpp row-threads in order and writes scale * total to
+// out[channel * 2 + (v >> 3)], channel = 8 g + (v & 7).
+__device__ __forceinline__ void fold_rows(const double* red, int cg, int rpp, int ld, double scale, double* out) {
+  for (int o = threadIdx.x; o < 16 * cg; o += 256) {
+    const int v = o / cg, g = o - v * cg;
+    const int c = 8 * g + (v & 7);
+    if (c >= ld) continue;
+    double a = 0.0;
+    for (int t = 0; t < rpp; ++t) a += red[v * 256 + t * cg + g];
+    out[c * 2 + (v >> 3)] = scale * a;
+  }
+}
+
 // ------------------------------------------------------------------ forward
 // grid (nsplit, W). scratch[((rep * nsplit + split) * ld + c) * 2 + {0, 1}] = sum x, sum x^2 over the split's rows.
 template <typename T>
@@ -113,17 +128,7 @@ __global__ __launch_bounds__(256) void bn_fwd_stats_kernel(BnParams p) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) { red[i * 256 + threadIdx.x] = s[i]; red[(8 + i) * 256 + threadIdx.x] = ss[i]; }
   __syncthreads();
-  if (l.active && l.tr == 0) {
-    double* out = p.scratch + (((size_t)blockIdx.y * gridDim.x + blockIdx.x) * p.ld + l.c0) * 2;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (l.c0 + i >= p.ld) break;
-      double a = 0.0, b = 0.0;
-      for (int t = 0; t < l.rpp; ++t) { a += red[i * 256 + t * cg + l.tg]; b += red[(8 + i) * 256 + t * cg + l.tg]; }
-      out[2 * i] = a;
-      out[2 * i + 1] = b;
-    }
-  }
+  fold_rows(red, cg, l.rpp, p.ld, 1.0, p.scratch + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * p.ld * 2);
 }
 
 // grid (ceil(ld / 16), W), 256 threads = 16 split lanes x 16 channels: folds the nsplit partial sums of a
@@ -291,17 +296,7 @@ __global__ __launch_bounds__(256) void bn_bwd_stats_kernel(BnParams p) {
 #pragma unroll
   for (int i = 0; i < 8; ++i) { red[i * 256 + threadIdx.x] = s[i]; red[(8 + i) * 256 + threadIdx.x] = ss[i]; }
   __syncthreads();
-  if (l.active && l.tr == 0) {
-    double* out = p.scratch + (((size_t)rep * gridDim.x + blockIdx.x) * p.ld + l.c0) * 2;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if (l.c0 + i >= p.ld) break;
-      double a = 0.0, b = 0.0;
-      for (int t = 0; t < l.rpp; ++t) { a += red[i * 256 + t * cg + l.tg]; b += red[(8 + i) * 256 + t * cg + l.tg]; }
-      out[2 * i] = (double)p.alpha * a;
-      out[2 * i + 1] = (double)p.alpha * b;
-    }
-  }
+  fold_rows(red, cg, l.rpp, p.ld, (double)p.alpha, p.scratch + ((size_t)rep * gridDim.x + blockIdx.x) * p.ld * 2);
 }
 
 // grid (nsplit, W): streams dx from dy, x, the saved statistics and the finished dgamma / dbeta totals.
