@@ -542,7 +542,8 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
         w.R = L.R; w.S = L.R; w.stride = L.stride; w.pad = L.pad;
         w.NK = L.RS * L.Cinpad;
         w.P = P;
-        L.nsplit = wgrad_choose_split(c.dt, w, c.W);
+        // with three or more module programs on concurrent streams a wgrad launch need not fill the chip alone
+        L.nsplit = wgrad_choose_split(c.dt, w, c.W, c.K >= 3 ? 128 : 256);
       }
       L.partial = (float*)A.take((size_t)L.nsplit * L.pstride * 4);
       if (L.need_stash) {

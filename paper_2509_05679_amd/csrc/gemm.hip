@@ -1563,14 +1563,16 @@ int launch_wgrad(int dt, const WgradParams& p, hipStream_t s) {
   return dt == DT_F32 ? launch_wgrad_t<float>(p, s) : launch_wgrad_t<bf16_t>(p, s);
 }
 
-int wgrad_choose_split(int dt, const WgradParams& shape, int W) {
+int wgrad_choose_split(int dt, const WgradParams& shape, int W, int target_wgs) {
   const int Mout = shape.Mout, NK = shape.NK, P = shape.P;
   const int per_replica = P / W;  // pixels of one replica's mini-batch
   if (dt != DT_F32) {
-    // Asynchronous kernel: 64 x 64 output blocks per (sub-pixel, channel block); splits are whole
-    // 128-pixel tiles. Take the fewest splits that give every CU a workgroup: the partial sums
-    // cost HBM traffic (written here, read by the update) in proportion to the split count, and
-    // measured on the ResNet-18 step 256 workgroups beat 512 and 1024 (2.95 / 3.13 / 3.45 ms).
+    // Asynchronous kernel: 64 x 64 output blocks per (sub-pixel, channel block); a data-group's 128-pixel
+    // tiles are dealt to its splits. Take the fewest splits that give the launch target_wgs workgroups:
+    // the partial sums cost HBM traffic (written here, read by the update) in proportion to the split
+    // count. Measured on the ResNet-18 step with four modules on four streams: 1024 / 512 / 256 / 128 / 64
+    // workgroups -> 3.45 / 3.13 / 2.64 / 2.53 / 2.54 ms; with two modules (ResNet-20 shapes) 256 beats 128
+    // (1.55 vs 1.74 ms): the caller passes 128 when three or more modules share the chip, else 256.
     WgradParams probe = shape;
     probe.nsplit = W;
     probe.nrep = W;
@@ -1578,7 +1580,7 @@ int wgrad_choose_split(int dt, const WgradParams& shape, int W) {
     if (wgrad_dma_eligible(probe, &nsub, &cblocks)) {
       const int blocks = cdiv(Mout, 64) * nsub * cblocks;
       const int rep_tiles = per_replica / 128;
-      int q = cdiv(256, blocks * W);
+      int q = cdiv(target_wgs, blocks * W);
       if (q > rep_tiles) q = rep_tiles;
       if (q * W > 256) q = 256 / W;
       if (q < 1) q = 1;
@@ -1589,7 +1591,7 @@ int wgrad_choose_split(int dt, const WgradParams& shape, int W) {
   const int ce = dtype_ce(dt);
   const int bke = 128 / dtype_size(dt);
   int tiles = (Mout <= 64) ? cdiv(Mout, 64) * cdiv(NK + ce, 256) : cdiv(Mout, 128) * cdiv(NK + ce, 128);
-  int q = cdiv(1024, tiles * W);  // aim at ~1024 workgroups
+  int q = cdiv(1024, tiles * W);  // aim at ~1024 workgroups (512 and 256 measured slower on the fp32 CNN: 2.33-2.35 vs 2.25 ms)
   int qmax = per_replica / (2 * bke);  // at least two k-tiles per split
   if (qmax < 1) qmax = 1;
   if (q > qmax) q = qmax;

@@ -139,7 +139,8 @@ int launch_wgrad(int dt, const WgradParams& p, hipStream_t s);
 // count W, so that no split mixes two replicas. shape: every field that describes the layer
 // (Nimg, H, W, Cx, Ho, Wo, Mout, ldy, R, S, stride, pad, NK, P, zeros non-null); nsplit,
 // pix_per_split and the pointers are ignored.
-int wgrad_choose_split(int dt, const WgradParams& shape, int W);
+// target_wgs: workgroups the asynchronous kernel's launch should reach (fewer splits = less partial-sum traffic).
+int wgrad_choose_split(int dt, const WgradParams& shape, int W, int target_wgs);
 
 void launch_ingest(int dt, const IngestParams& p, hipStream_t s);
 void launch_maxpool_fwd(int dt, const void* x, void* y, int N, int H, int W, int C, hipStream_t s);
