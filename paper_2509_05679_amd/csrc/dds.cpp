@@ -251,7 +251,6 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
   int res_in = -1;  // block input tensor while inside a residual block
   for (int i = lo; i < hi; ++i) {
     const dds_layer& L = sp.layers[i];
-    const bool next_is = i + 1 < hi;
     switch (L.op) {
       case DDS_OP_CONV2D:
       case DDS_OP_LINEAR: {
@@ -388,7 +387,6 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
       default:
         return fail(DDS_EINVAL, "layer %d: unknown op %d", i, L.op);
     }
-    (void)next_is;
   }
   if (res_in >= 0) return fail(DDS_EINVAL, "module %d ends inside a residual block", k0);
   if (k0 == K - 1) {
@@ -482,7 +480,7 @@ int plan_module(const dds_spec& sp, int k0, int K, int N, int dt, const Tensor* 
   return DDS_OK;
 }
 
-int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
+int layout(dds_ctx& c, Arena& A) {
   const int es = dtype_size(c.dt);
   for (int k0 = 0; k0 < c.K; ++k0) {
     Module& m = c.mods[k0];
@@ -576,7 +574,6 @@ int layout(dds_ctx& c, const dds_spec& sp, Arena& A) {
   c.loss = (float*)A.take(sizeof(float) * c.W);
   c.zeros = A.take(kZeroBytes);
   if (c.gossip) c.P_dev = (float*)A.take(sizeof(float) * c.W * c.W);
-  (void)sp;
   return DDS_OK;
 }
 
@@ -630,8 +627,6 @@ int build(dds_ctx& c, const dds_spec* sp, int K, int W, const int* delays) {
     const Tensor* in = k0 ? &c.mods[k0 - 1].tensors[c.mods[k0 - 1].out_tensor] : nullptr;
     rc = plan_module(*sp, k0, K, c.N, c.dt, in, m);
     if (rc) return rc;
-    bool has_params = !m.layers.empty();
-    (void)has_params;
   }
   // sizes that index arithmetic in the kernels keeps in 32 bits
   for (Module& m : c.mods)
@@ -1008,7 +1003,7 @@ int dds_arena_bytes(const dds_spec* spec, int K, int W, const int* delays, size_
   if (rc) return rc;
   Arena A;
   A.dry = true;
-  rc = layout(c, *spec, A);
+  rc = layout(c, A);
   if (rc) return rc;
   *bytes = align_up(A.used, 256);
   return DDS_OK;
@@ -1022,7 +1017,7 @@ int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* aren
   int rc = build(*c, spec, K, W, delays);
   if (rc) { delete c; return rc; }
   Arena dry;
-  layout(*c, *spec, dry);
+  layout(*c, dry);
   if (align_up(dry.used, 256) > arena_bytes) {
     size_t need = align_up(dry.used, 256);
     delete c;
@@ -1037,7 +1032,7 @@ int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* aren
   c = new dds_ctx();
   rc = build(*c, spec, K, W, delays);
   if (rc) { delete c; return rc; }
-  layout(*c, *spec, A);
+  layout(*c, A);
   c->arena_used = align_up(A.used, 256);
   c->gemm_flops = count_flops(*c);
   hipError_t e = hipMemset(arena, 0, c->arena_used);

@@ -1323,6 +1323,8 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
 #pragma unroll
   for (int e = 0; e < 16; ++e) accb[e] = 0.f;
   const uint4 ones = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+  // narrow layers (at most 32 output or input channels): the waves of the empty half-blocks skip the arithmetic
+  const bool idle_wave = k0 + wave_m * 32 >= p.Mout || c0 + wave_n * 32 >= p.Cx;
 
   for (int t = 0; t < ntiles; ++t) {
     wait_vm<NF>();  // everything but the youngest tile's fills has landed
@@ -1358,6 +1360,7 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
         bf[set][tap] = make_uint4(b0.x, b0.y, b1.x, b1.y);
       }
     };
+    if (idle_wave) continue;  // its 32 x 32 block lies past the real channels: fills and barriers only
     load_frags(0, 0);
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
