@@ -13,11 +13,14 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 # Guard rail on single tensors, measured against the accumulated update (see test_gpu_parity.py):
 # applied in fp32, where it holds every tensor of every normalised net below (also at the full
 # channel counts and image sizes) to <= 2e-2, i.e. the algebra is right. In bf16 it is reported but
-# not asserted: the backward of a normalisation subtracts the per-channel mean and the xhat
-# component from an error gradient that was rounded to bf16 (2^-9 of its *full* magnitude), so the
-# error relative to the much smaller projected gradient -- and to the update built from it -- is
-# amplified well beyond a few bf16 ulps (0.1-0.4 observed on single tensors). The stated bar,
-# relative error of every layer weight vector <= 2e-2, is asserted in both precisions.
+# not asserted: the library stores the convolution output in bf16 before normalising it, and for the
+# elements whose normalised value lies within that quantisation step of zero the ReLU decision differs
+# from the fp64 oracle's (0.1-0.3 % of the elements). Each such flip changes the back-propagated
+# gradient by its full value at that element, so the gradients upstream of a normalised ReLU move by
+# about sqrt(fraction) = 3-6 % per such layer (0.1-0.4 observed on single tensors after several), while
+# gamma / beta of the layer itself move by tenths of a percent. tests/test_oracle_network.py reproduces
+# the effect inside the oracle by quantising that one tensor. The stated bar, relative error of every
+# layer weight vector <= 2e-2, is asserted in both precisions.
 UPDATE_TOL = {"f32": 2e-2, "bf16": float("inf")}
 # A convolution bias that feeds a normalisation has an exactly zero gradient in exact arithmetic
 # (the normalisation removes any per-channel constant): the oracle leaves it at ~1e-17, fp32 /
