@@ -251,14 +251,15 @@ def odd_resnet(precision="f32", K=2, W=2, B=3, h=7, w=9, c=16, steps=8) -> Workl
                     momentum=0.0, steps=steps, extra={"blocks": 2, "res_scale": scale})
 
 
-def tiny_cnn(K=2, W=2, B=4, hw=8, c=4, precision="f32", steps=8, momentum=0.9) -> Workload:
-    """conv-relu-maxpool x2, gap, linear: the cfg1 structure at toy size."""
-    ops = [_conv(3, c), _relu(), {"op": "maxpool2"}]
+def tiny_cnn(K=2, W=2, B=4, hw=8, c=4, precision="f32", steps=8, momentum=0.9, bn=False) -> Workload:
+    """conv-relu-maxpool x2, gap, linear: the cfg1 structure at toy size (bn: a batch normalisation
+    after each convolution)."""
+    ops = [_conv(3, c), *([_bn(c)] if bn else []), _relu(), {"op": "maxpool2"}]
     cut = len(ops)
-    ops += [_conv(c, 2 * c), _relu(), {"op": "maxpool2"}, {"op": "gap"}, _linear(2 * c, 10),
-            {"op": "softmax_ce"}]
+    ops += [_conv(c, 2 * c), *([_bn(2 * c)] if bn else []), _relu(), {"op": "maxpool2"}, {"op": "gap"},
+            _linear(2 * c, 10), {"op": "softmax_ce"}]
     bounds = [0, len(ops)] if K == 1 else [0, cut, len(ops)]
-    return Workload(name=f"tiny_cnn_K{K}", ops=ops, bounds=bounds, K=K, W=W, B=B,
+    return Workload(name=f"tiny_cnn_K{K}" + ("_bn" if bn else ""), ops=ops, bounds=bounds, K=K, W=W, B=B,
                     in_shape=(3, hw, hw), classes=10, precision=precision, lr=0.05,
                     momentum=momentum, steps=steps)
 

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 from dds_inputs import workload
-from dds_inputs.configs import ring_mixing, tiny_resnet
+from dds_inputs.configs import ring_mixing, tiny_cnn, tiny_resnet
 from parity import flat_init, rel_errors, run_hip, run_oracle, tensor_slices
 
 pytestmark = pytest.mark.gpu
@@ -78,6 +78,11 @@ def test_channel_counts_off_the_eight_channel_grid_fp32():
     # 4 and 12 channels: fp32 rows whose last group of eight is half empty
     _compare(tiny_resnet(K=2, W=2, B=3, c=4, bn=True), seed=23, T=6, update_tol=1e-3)
     _compare(tiny_resnet(K=2, W=3, B=5, c=6, hw=6, bn=True), seed=24, T=6, update_tol=1e-3)
+
+
+def test_normalisation_in_front_of_max_pooling_with_momentum_fp32():
+    # conv - bn - relu - maxpool: the pooling backward masks by the normalised ReLU output; momentum 0.9
+    _compare(tiny_cnn(K=2, W=2, B=4, bn=True), seed=30, T=8, update_tol=1e-3)
 
 
 def test_tiny_resnet_bn_bf16():

@@ -121,3 +121,10 @@ def test_ring_of_four_resnet18_shapes_bf16():
     # the MFMA kernels launched once per data-group (4 images each) with that group's own weights and snapshots
     wl = workload("cfg2_resnet18", B=4)
     _compare(wl, seed=16, T=2 * (wl.K - 1) + 6, mixing=ring_mixing(4, 0.3))
+
+
+def test_ring_of_four_cnn_shapes_fp32():
+    # fp32 arithmetic at the CNN configuration's layer shapes (64-512 channels, max-pooling, momentum 0.9):
+    # the fp32 asynchronous kernels with one launch per layer for the four data-groups' own weights
+    wl = workload("cfg1_cnn", B=8)
+    _compare(wl, seed=17, T=2 * (wl.K - 1) + 6, mixing=ring_mixing(4, 0.3))
