@@ -654,7 +654,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) =
   // Rows outside the image and surplus fills read the zero block.
   // (table entries are read in one batch and turned into addresses with selects: a branch per
   // entry would serialise one LDS round trip per fill at the very start of the kernel)
-  constexpr int NPRO = 7;  // fills per wave that cover the largest patch (4 waves x 7 x FROWS rows)
+  constexpr int NPRO = (KB == 128 && PS == 0) ? 11 : 7;  // fills per wave that cover the largest patch (4 waves x NPRO x FROWS rows)
   const char* pro_src[NPRO];
   {
     int offs[NPRO];
@@ -931,7 +931,7 @@ bool launch_dma_inst(const ConvParams& p, const HaloGeom& h, hipStream_t s) {
   const int fills_per_wave = (dg.patch_rows / FROWS + NW - 1) / NW;
   if (p.Cx * (int)sizeof(T) % KB != 0) return false;
   const int nchunks = p.Cx * (int)sizeof(T) / KB;
-  if (fills_per_wave > 7) return false;  // the kernel keeps seven prologue sources per lane
+  if (fills_per_wave > ((KB == 128 && PS == 0) ? 11 : 7)) return false;  // prologue sources kept per lane
   if (PS == 0 ? nchunks != 1 : (nchunks < 2 || 7 * PS < fills_per_wave)) return false;
   const int smem = dg.tab_bytes + (PS > 0 ? 2 : 1) * dg.patch_rows * KB + 3 * BN * KB + 1024;
   if (smem > 160 * 1024 || p.zeros == nullptr) return false;
@@ -962,6 +962,10 @@ bool launch_dma(const ConvParams& p, hipStream_t s) {
   const int rowbytes = p.Cx * (int)sizeof(T);
   if (rowbytes % KB != 0) return false;
   const int nchunks = rowbytes / KB;
+  // 64 bf16 (32 fp32) channels in and at most 64 out: one 128-byte chunk, i.e. whole cache lines per patch row,
+  // nine stages instead of eighteen and the whole patch requested in the prologue (62.0 -> 59.4 us at 32 x 32 x 64)
+  if (rowbytes == 128 && p.ldy <= 64 && halo_geometry<T>(p, h, 256, 128) &&
+      launch_dma_inst<T, 256, 64, 64, 64, 0, 128>(p, h, s)) return true;
   if (nchunks == 1) {
     if (!halo_geometry<T>(p, h, 256, KB)) return false;
     if (p.ldy <= 64) return launch_dma_inst<T, 256, 64, 64, 64, 0, KB>(p, h, s);
