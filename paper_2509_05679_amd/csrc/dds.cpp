@@ -163,6 +163,7 @@ struct dds_ctx {
   int64_t t = 0;
   bool have_loss = false;
   hipEvent_t fork = nullptr;
+  std::vector<hipStream_t> pool;  // internal streams; module k0 runs on the caller's stream if k0 % (pool+1) == 0
   int64_t launches = 0;
   double gemm_flops = 0.0;
   size_t arena_used = 0;
@@ -1046,11 +1047,25 @@ int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* aren
   e = hipEventCreateWithFlags(&c->fork, hipEventDisableTiming);
   if (e != hipSuccess) { delete c; return fail(DDS_EHIP, "hipEventCreate failed: %s", hipGetErrorString(e)); }
   if (K > 1) {
-    for (Module& m : c->mods) {
-      if (hipStreamCreateWithFlags(&m.stream, hipStreamNonBlocking) != hipSuccess ||
-          hipEventCreateWithFlags(&m.done, hipEventDisableTiming) != hipSuccess) {
+    // As many streams as the runtime has hardware queues (GPU_MAX_HW_QUEUES, 4 unless set), the caller's
+    // included: a stream beyond that lands on a queue already in use and the two programs on it run one
+    // after the other anyway -- better to choose which modules share. Module k0 -> stream k0 mod n.
+    int nq = 4;
+    if (const char* q = getenv("GPU_MAX_HW_QUEUES")) { const int v = atoi(q); if (v >= 1 && v <= 32) nq = v; }
+    const int ns = K < nq ? K : nq;
+    c->pool.resize(ns - 1, nullptr);
+    for (hipStream_t& st : c->pool)
+      if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) {
         dds_destroy(c);
-        return fail(DDS_EHIP, "stream/event creation failed");
+        return fail(DDS_EHIP, "stream creation failed");
+      }
+    for (int k0 = 0; k0 < K; ++k0) {
+      Module& m = c->mods[k0];
+      if (k0 % ns == 0) continue;  // on the caller's stream
+      m.stream = c->pool[k0 % ns - 1];
+      if (hipEventCreateWithFlags(&m.done, hipEventDisableTiming) != hipSuccess) {
+        dds_destroy(c);
+        return fail(DDS_EHIP, "event creation failed");
       }
     }
   }
@@ -1063,9 +1078,10 @@ int dds_destroy(dds_ctx* c) {
   if (!c) return DDS_OK;
   (void)hipDeviceSynchronize();
   for (Module& m : c->mods) {
-    if (m.stream) (void)hipStreamDestroy(m.stream);
     if (m.done) (void)hipEventDestroy(m.done);
   }
+  for (hipStream_t st : c->pool)
+    if (st) (void)hipStreamDestroy(st);
   if (c->fork) (void)hipEventDestroy(c->fork);
   for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
   delete c;
@@ -1165,8 +1181,10 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
   if (multi) HIP_TRY(hipEventRecord(c->fork, us));
   for (int k0 = 0; k0 < c->K; ++k0) {
     Module& m = c->mods[k0];
-    hipStream_t s = multi ? m.stream : us;
-    if (multi) HIP_TRY(hipStreamWaitEvent(s, c->fork, 0));
+    // module programs on an internal stream fork from the caller's stream and are joined to it after the loop
+    const bool own = multi && m.stream != nullptr;
+    hipStream_t s = own ? m.stream : us;
+    if (own) HIP_TRY(hipStreamWaitEvent(s, c->fork, 0));
     const int64_t f = t - k0, b = t - k0 - 2 * m.d;
     const bool last = k0 == c->K - 1;
     if (f >= 0) run_forward(*c, m, t, f, s);
@@ -1202,11 +1220,11 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
       launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, (int)((t + 1) % m.R), s);
       c->launches += 2;
     }
-    if (multi) {
-      HIP_TRY(hipEventRecord(m.done, s));
-      HIP_TRY(hipStreamWaitEvent(us, m.done, 0));
-    }
+    if (own) HIP_TRY(hipEventRecord(m.done, s));
   }
+  if (multi)
+    for (Module& m : c->mods)
+      if (m.stream) HIP_TRY(hipStreamWaitEvent(us, m.done, 0));
   HIP_TRY(hipGetLastError());
   c->t = t + 1;
   if (c->profiling) {  // harvest this step's event pairs (synchronises: profiling runs are not timed runs)
