@@ -1577,9 +1577,10 @@ int wgrad_choose_split(int dt, const WgradParams& shape, int W, int target_wgs) 
     // Asynchronous kernel: 64 x 64 output blocks per (sub-pixel, channel block); a data-group's 128-pixel
     // tiles are dealt to its splits. Take the fewest splits that give the launch target_wgs workgroups:
     // the partial sums cost HBM traffic (written here, read by the update) in proportion to the split
-    // count. Measured on the ResNet-18 step with four modules on four streams: 1024 / 512 / 256 / 128 / 64
-    // workgroups -> 3.45 / 3.13 / 2.64 / 2.53 / 2.54 ms; with two modules (ResNet-20 shapes) 256 beats 128
-    // (1.55 vs 1.74 ms): the caller passes 128 when three or more modules share the chip, else 256.
+    // count. Measured on the ResNet-18 step (four modules on four hardware queues): 1024 / 512 workgroups cost
+    // 3.45 / 3.13 ms against 2.64 at 256 under an earlier stream layout; now 64 / 128 / 192 / 256 -> 2.59 / 2.47 /
+    // 2.46 / 2.48 ms. With two modules (ResNet-20 shapes) 256 beats 128 (1.47 vs 1.67 ms): the caller passes 128
+    // when three or more modules share the chip (half the partial-sum traffic at equal speed), else 256.
     WgradParams probe = shape;
     probe.nsplit = W;
     probe.nrep = W;
