@@ -147,7 +147,11 @@ int dds_consensus_error(dds_ctx* ctx, double* host_out, void* hip_stream);
  * y_device[s]: its targets, int32 [B], values in [0,classes). Both arrays of
  * pointers are host arrays of W device pointers, borrowed: they are read only by the
  * ingest kernel enqueued by this call. lr: step size for this iteration, or NaN to
- * use spec.lr. Asynchronous on stream. */
+ * use spec.lr. Asynchronous on stream: the K module programs run on stream and on internal
+ * non-blocking streams (as many streams in all as the runtime has hardware queues, see
+ * GPU_MAX_HW_QUEUES; default priority) that fork from stream after the ingest and are
+ * joined to it before the call returns, so work enqueued on stream afterwards sees the
+ * whole iteration. */
 int dds_step(dds_ctx* ctx, const float* const* x_device, const int32_t* const* y_device, float lr,
              void* hip_stream);
 
