@@ -149,9 +149,12 @@ int dds_consensus_error(dds_ctx* ctx, double* host_out, void* hip_stream);
  * ingest kernel enqueued by this call. lr: step size for this iteration, or NaN to
  * use spec.lr. Asynchronous on stream: the K module programs run on stream and on internal
  * non-blocking streams (as many streams in all as the runtime has hardware queues, see
- * GPU_MAX_HW_QUEUES; default priority) that fork from stream after the ingest and are
- * joined to it before the call returns, so work enqueued on stream afterwards sees the
- * whole iteration. */
+ * GPU_MAX_HW_QUEUES; default priority). All of them are joined to stream before the call
+ * returns, so work enqueued on stream afterwards sees the whole iteration. A program on an
+ * internal stream is ordered after the caller's earlier work on stream in the first
+ * iteration and in any iteration that follows a dds_get_params* / dds_set_params /
+ * dds_consensus_error / dds_profile call; otherwise (three or more modules) only after the
+ * previous iteration of its two neighbour modules, which is all it depends on. */
 int dds_step(dds_ctx* ctx, const float* const* x_device, const int32_t* const* y_device, float lr,
              void* hip_stream);
 

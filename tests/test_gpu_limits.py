@@ -88,3 +88,37 @@ def test_error_paths_of_context_calls():
     out = C.c_void_p()
     base = (arena.data_ptr() + 255) // 256 * 256
     assert lib.dds_create(C.byref(spec.c), wl.K, wl.W, None, base, need // 2, C.byref(out)) == P.DDS_ENOMEM
+
+
+@pytest.mark.parametrize("name,B,steps", [("cfg2_resnet18", 16, 40), ("cfg3_resnet56", 4, 40), ("cfg1_cnn", 16, 30)])
+def test_run_ahead_across_iterations_is_bit_identical_to_serial_execution(name, B, steps):
+    """With three or more modules a module program starts as soon as its neighbours' previous iteration is
+    done, i.e. before the other modules have finished the current one. Batches are resident and the steps are
+    enqueued back to back so that the programs really overlap across iterations; the result must equal, bit
+    for bit, the run in which the modules execute one after another on the caller's stream."""
+    import torch
+    import paper_2509_05679_amd as P
+    from dds_inputs import workload
+    wl = workload(name, B=B)
+    init = make_params(wl, 7)
+    pool = 5
+    xs = [[torch.from_numpy(make_batch(wl, 7, t, s)[0]).cuda() for s in range(wl.W)] for t in range(pool)]
+    ys = [[torch.from_numpy(make_batch(wl, 7, t, s)[1]).cuda() for s in range(wl.W)] for t in range(pool)]
+
+    def run(mode):
+        tr = P.Trainer(P.Spec.from_workload(wl), wl.W)
+        for k0 in range(wl.K):
+            tr.dds_set_params(k0, init[k0])
+        if mode:
+            tr.dds_profile(mode)
+        for t in range(steps):
+            tr.dds_step(xs[t % pool], ys[t % pool])
+        torch.cuda.synchronize()
+        out = [tr.dds_get_params(k0) for k0 in range(wl.K)]
+        tr.close()
+        return out
+
+    ahead, serial = run(0), run(2)
+    for k0 in range(wl.K):
+        assert np.isfinite(ahead[k0]).all()
+        assert np.array_equal(ahead[k0], serial[k0]), f"module {k0}"
