@@ -205,6 +205,7 @@ def main():
                    "consensus_error": tr.dds_consensus_error() if mixing is not None else 0.0},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": traffic,
+                     "conv_mfma_util_pct_of_peak": 100.0 * achieved / peak,
                      "kernel": dom_name,
                      "avg_launch_us": 1e3 * gemm_ms / max(gemm_launches, 1), "per_class": per_class,
                      "all_gemm_launches": {"TFLOP/s": all_fl / max(all_ms, 1e-9) / 1e9, "avg_us": 1e3 * all_ms / max(all_n, 1),
