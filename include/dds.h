@@ -154,7 +154,9 @@ int dds_consensus_error(dds_ctx* ctx, double* host_out, void* hip_stream);
  * internal stream is ordered after the caller's earlier work on stream in the first
  * iteration and in any iteration that follows a dds_get_params* / dds_set_params /
  * dds_consensus_error / dds_profile call; otherwise (three or more modules) only after the
- * previous iteration of its two neighbour modules, which is all it depends on. */
+ * previous iteration of its two neighbour modules, which is all it depends on. stream may
+ * differ from call to call: an iteration is then ordered after the previous one by the
+ * library. */
 int dds_step(dds_ctx* ctx, const float* const* x_device, const int32_t* const* y_device, float lr,
              void* hip_stream);
 

@@ -166,6 +166,8 @@ struct dds_ctx {
   // True while the done events of the previous iteration describe everything a module program depends on:
   // cleared by every call that touches module state from the caller's stream outside dds_step.
   bool chained = false;
+  hipStream_t last_stream = nullptr;  // stream of the previous dds_step
+  hipEvent_t step_end = nullptr;      // recorded on it after that step's joins
   std::vector<hipStream_t> pool;  // internal streams; module k0 runs on the caller's stream if k0 % (pool+1) == 0
   int64_t launches = 0;
   double gemm_flops = 0.0;
@@ -1048,7 +1050,8 @@ int dds_create(const dds_spec* spec, int K, int W, const int* delays, void* aren
     c->serial = env && env[0] == '1';
   }
   e = hipEventCreateWithFlags(&c->fork, hipEventDisableTiming);
-  if (e != hipSuccess) { delete c; return fail(DDS_EHIP, "hipEventCreate failed: %s", hipGetErrorString(e)); }
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&c->step_end, hipEventDisableTiming);
+  if (e != hipSuccess) { dds_destroy(c); return fail(DDS_EHIP, "hipEventCreate failed: %s", hipGetErrorString(e)); }
   if (K > 1) {
     // As many streams as the runtime has hardware queues (GPU_MAX_HW_QUEUES, 4 unless set), the caller's
     // included: a stream beyond that lands on a queue already in use and the two programs on it run one
@@ -1087,6 +1090,7 @@ int dds_destroy(dds_ctx* c) {
   for (hipStream_t st : c->pool)
     if (st) (void)hipStreamDestroy(st);
   if (c->fork) (void)hipEventDestroy(c->fork);
+  if (c->step_end) (void)hipEventDestroy(c->step_end);
   for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
   delete c;
   return DDS_OK;
@@ -1171,6 +1175,10 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
   const int64_t t = c->t;
   const float step = std::isnan(lr) ? c->lr : lr;
   c->launches = 0;
+  if (t > 0 && us != c->last_stream) {  // the caller switched streams: order this iteration after the previous one
+    HIP_TRY(hipStreamWaitEvent(us, c->step_end, 0));
+    c->chained = false;
+  }
 
   // ingest: caller batches -> module 0's ring slot t mod R_0 (layout + precision), labels -> queue
   {
@@ -1244,6 +1252,8 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
       if (m.stream) HIP_TRY(hipStreamWaitEvent(us, m.done[t & 1], 0));
   // (with two modules the fork from the caller's stream measured 2.5 % faster than the chain)
   c->chained = multi && c->K >= 3;
+  HIP_TRY(hipEventRecord(c->step_end, us));
+  c->last_stream = us;
   HIP_TRY(hipGetLastError());
   c->t = t + 1;
   if (c->profiling) {  // harvest this step's event pairs (synchronises: profiling runs are not timed runs)

@@ -122,3 +122,38 @@ def test_run_ahead_across_iterations_is_bit_identical_to_serial_execution(name, 
     for k0 in range(wl.K):
         assert np.isfinite(ahead[k0]).all()
         assert np.array_equal(ahead[k0], serial[k0]), f"module {k0}"
+
+
+def test_switching_the_callers_stream_between_iterations():
+    """Module 0 runs on the caller's stream: when the caller passes another stream the library orders the new
+    iteration after the previous one itself. Alternating between two streams must not change a bit."""
+    import ctypes as C
+    import torch
+    import paper_2509_05679_amd as P
+    from dds_inputs import workload
+    wl = workload("cfg2_resnet18", B=8)
+    init = make_params(wl, 9)
+    xs = [torch.from_numpy(make_batch(wl, 9, 0, s)[0]).cuda() for s in range(wl.W)]
+    ys = [torch.from_numpy(make_batch(wl, 9, 0, s)[1]).cuda() for s in range(wl.W)]
+    side = torch.cuda.Stream()  # default priority
+    torch.cuda.synchronize()
+
+    def run(alternate):
+        tr = P.Trainer(P.Spec.from_workload(wl), wl.W)
+        for k0 in range(wl.K):
+            tr.dds_set_params(k0, init[k0])
+        torch.cuda.synchronize()
+        for t in range(16):
+            if alternate and t % 2:
+                with torch.cuda.stream(side):
+                    tr.dds_step(xs, ys)
+            else:
+                tr.dds_step(xs, ys)
+        torch.cuda.synchronize()
+        out = [tr.dds_get_params(k0) for k0 in range(wl.K)]
+        tr.close()
+        return out
+
+    same, alt = run(False), run(True)
+    for k0 in range(wl.K):
+        assert np.array_equal(same[k0], alt[k0]), f"module {k0}"
