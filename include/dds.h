@@ -125,7 +125,9 @@ int64_t dds_param_count(const dds_ctx* ctx, int module);
  * n_floats == dds_param_count) in canonical order, asynchronously on stream.
  * dds_set_params also refreshes the compute-precision copy and every weight
  * snapshot of the module and clears its momentum; call it before the first step
- * (Algorithm 1 input: the initial weights, identical in every data-group). */
+ * (Algorithm 1 input: the initial weights, identical in every data-group). Every call that
+ * reads or writes module state on a stream (these, dds_get_loss, dds_consensus_error) is ordered
+ * after the latest dds_step also when that stream is not the one dds_step was given. */
 int dds_get_params(dds_ctx* ctx, int module, float* dst_device, size_t n_floats, void* hip_stream);
 int dds_set_params(dds_ctx* ctx, int module, const float* src_device, size_t n_floats, void* hip_stream);
 

@@ -1105,6 +1105,12 @@ int64_t dds_step_count(const dds_ctx* c) { return c ? c->t : (int64_t)fail(DDS_E
 int64_t dds_launches_last_step(const dds_ctx* c) { return c ? c->launches : (int64_t)fail(DDS_EINVAL, "null ctx"); }
 double dds_gemm_flops_per_step(const dds_ctx* c) { return c ? c->gemm_flops : 0.0; }
 
+// Calls that read or write module state from a stream other than the last iteration's are ordered after it.
+static int order_after_last_step(dds_ctx* c, hipStream_t s) {
+  if (c->t > 0 && s != c->last_stream) HIP_TRY(hipStreamWaitEvent(s, c->step_end, 0));
+  return DDS_OK;
+}
+
 static int params_io(dds_ctx* c, int module, int replica, float* buf, size_t n_floats, void* stream, bool set) {
   if (!c || module < 0 || module >= c->K || !buf) return fail(DDS_EINVAL, "bad ctx / module / pointer");
   if (replica < 0 || replica >= c->W) return fail(DDS_EINVAL, "replica %d out of range [0,%d)", replica, c->W);
@@ -1114,6 +1120,7 @@ static int params_io(dds_ctx* c, int module, int replica, float* buf, size_t n_f
   if ((long long)n_floats != m.canon_params)
     return fail(DDS_EINVAL, "module %d has %lld parameters, caller passed %zu", module, m.canon_params, n_floats);
   hipStream_t s = (hipStream_t)stream;
+  if (int rc = order_after_last_step(c, s)) return rc;
   size_t off = 0;
   for (ParamLayer& L : m.layers) {
     launch_param_permute(buf + off, m.master + roff + L.off, L.Cout, L.Cin, L.RS, L.Cinpad, set ? 1 : 0, s);
@@ -1142,6 +1149,7 @@ int dds_consensus_error(dds_ctx* c, double* host_out, void* stream) {
   if (!c->gossip) return DDS_OK;
   c->chained = false;
   hipStream_t s = (hipStream_t)stream;
+  if (int rc = order_after_last_step(c, s)) return rc;
   double worst = 0.0;
   std::vector<double> host, sums;
   for (Module& m : c->mods) {
@@ -1296,6 +1304,7 @@ int dds_get_loss(dds_ctx* c, float* host_out, void* stream) {
   if (!c || !host_out) return fail(DDS_EINVAL, "dds_get_loss: null argument");
   if (!c->have_loss) return fail(DDS_EINVAL, "no loss yet: the last module has not forwarded a mini-batch");
   float tmp[32];
+  if (int rc = order_after_last_step(c, (hipStream_t)stream)) return rc;
   HIP_TRY(hipMemcpyAsync(tmp, c->loss, sizeof(float) * c->W, hipMemcpyDeviceToHost, (hipStream_t)stream));
   HIP_TRY(hipStreamSynchronize((hipStream_t)stream));
   double acc = 0;
