@@ -1165,8 +1165,8 @@ __global__ __launch_bounds__(256, 2) void wgrad_gemm_kernel(WgradParams p) {
 // dW[k][tap][c] = sum over pixels p of dY[p][k] * X[p + tap][c]. The workgroup owns a
 // 64(k) x 64(c) block for ALL nine taps and walks its split of the pixel axis in tiles of
 // 128 pixels (rows of one image, or whole small images): per tile the dY rows and the X
-// patch with halo are copied global -> LDS in their natural [pixel][channel] order (ring
-// of three tiles, filled two tiles ahead) and the nine taps reuse them. The reduction
+// patch with halo are copied global -> LDS in their natural [pixel][channel] order (two
+// slots: the next tile is copied while this one is multiplied) and the nine taps reuse them. The reduction
 // index of this GEMM is the pixel, which is the slow axis of both operands in memory:
 // ds_read_b64_tr_b16 hands each lane four pixels of one channel from a 4 x 16 block, so
 // no register or LDS transposition is needed. 16-byte LDS columns are XOR-ed with
@@ -1214,7 +1214,11 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
   constexpr int SLOT = 16384 + PROW * 128;
   extern __shared__ __align__(16) char smem[];
   const uint32_t lds_ring = (uint32_t)(size_t)(DDS_LDS_AS char*)smem;
-  const uint32_t lds_dump = lds_ring + 3 * SLOT;
+  // Tiles in flight in LDS. Two (the next tile is copied while this one is multiplied) keep a workgroup at 85 KB,
+  // so that a conv workgroup of another module fits on the same CU; a third slot (copies two tiles ahead,
+  // 127 KB) was 1-2 % slower per training step on every configuration although each launch alone was not.
+  constexpr int RING = 2;
+  const uint32_t lds_dump = lds_ring + RING * SLOT;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1286,7 +1290,7 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
 
   // the first two tiles are requested before the rest of the set-up, which runs under their latency
   fill_tile(0, 0);
-  fill_tile(1, 1);
+  if (RING == 3) fill_tile(1, 1);
 
   // fragment addressing (see lds_tr16): lane -> (16-lane group, row inside the 4-row block, 8-byte segment)
   const int lq = lane & 15, grp16 = (lane >> 4) & 1, khalf = lane >> 5;
@@ -1333,16 +1337,17 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
   const bool idle_wave = k0 + wave_m * 32 >= p.Mout || c0 + wave_n * 32 >= p.Cx;
 
   for (int t = 0; t < ntiles; ++t) {
-    wait_vm<NF>();  // everything but the youngest tile's fills has landed
+    if (RING == 3) wait_vm<NF>();  // everything but the youngest tile's fills has landed
+    else wait_vm<0>();
     wg_barrier();
-    fill_tile(t + 2, (t + 2) % 3);
-    uint32_t ybuf = lds_ring + (t % 3) * SLOT + a_lane;
+    fill_tile(t + RING - 1, (t + RING - 1) % RING);
+    uint32_t ybuf = lds_ring + (t % RING) * SLOT + a_lane;
     uint32_t bp[2][4];
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        bp[hh][v] = lds_ring + (t % 3) * SLOT + 16384 + baddr[hh][v];
+        bp[hh][v] = lds_ring + (t % RING) * SLOT + 16384 + baddr[hh][v];
         // opaque: otherwise every (lane part + compile-time part) sum is precomputed outside the
         // tile loop, one register each, instead of riding in the instruction's offset field
         asm volatile("" : "+v"(bp[hh][v]));
@@ -1481,7 +1486,7 @@ void launch_wgrad_dma_inst(const WgradParams& p, const WgradGeom& wg, int nsub, 
     (void)hipFuncSetAttribute((const void*)wgrad_dma_kernel<TWLOG, THLOG, S2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     attr_set = true;
   }
-  const int smem = 3 * (16384 + PROW * 128) + 1024;
+  const int smem = 2 * (16384 + PROW * 128) + 1024;  // RING slots + dump block
   dim3 grid(cdiv(p.Mout, 64), nsub * wg.cblocks, p.nsplit);
   wgrad_dma_kernel<TWLOG, THLOG, S2><<<grid, S2 ? 256 : 768, smem, s>>>(p, wg, p.zeros);
 }
