@@ -85,6 +85,9 @@ def main():
     ap.add_argument("--workload", default="cfg2_resnet18")
     ap.add_argument("--batch", type=int, default=None, help="override per-replica batch (debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--activations", default="store", choices=["store", "recompute"],
+                    help="what delayed modules keep between forward and backward: every saved tensor (default) or "
+                         "input, output and a parameter snapshot, with a second forward pass before the backward")
     ap.add_argument("--mixing", default="mean",
                     help="'mean' (the headline path: exact averaging, one weight copy) or 'ring:ALPHA' "
                          "(ring communication graph, every data-group keeps its own weights)")
@@ -108,7 +111,7 @@ def main():
         if kind != "ring" or not alpha:
             sys.exit("bench.py: --mixing takes 'mean' or 'ring:ALPHA'")
         mixing = ring_mixing(wl.W, float(alpha))
-    spec = P.Spec.from_workload(wl, mixing)
+    spec = P.Spec.from_workload(wl, mixing, args.activations)
     tr = P.Trainer(spec, wl.W)
     init = make_params(wl, 0)
     for k0 in range(wl.K):
@@ -201,7 +204,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: K={wl.K} modules, W={wl.W} replicas x batch {wl.B}, {wl.precision}",
                    "launches_per_step": launches, "wall_ms_per_step": wall * 1e3 / args.steps,
-                   "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30, "mixing": args.mixing,
+                   "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30, "mixing": args.mixing, "activations": args.activations,
                    "consensus_error": tr.dds_consensus_error() if mixing is not None else 0.0},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": traffic,

@@ -59,6 +59,7 @@ enum {
 };
 
 enum { DDS_F32 = 0, DDS_BF16_F32MASTER = 1 };
+enum { DDS_ACT_STORE = 0, DDS_ACT_RECOMPUTE = 1 };
 
 typedef struct dds_layer {
   int32_t op;
@@ -83,6 +84,16 @@ typedef struct dds_spec {
                               1, entries in [0,1]); each data-group then keeps its own weights and
                               Section 3.3's update u_s = w_s - lr g_s, w_s <- sum_r P[s][r] u_r runs
                               as written. Read during dds_arena_bytes / dds_create only. */
+  int32_t activations;     /* DDS_ACT_STORE | DDS_ACT_RECOMPUTE: what a module with delay d > 0 keeps for the
+                              2d iterations between the forward and the backward pass of a mini-batch
+                              (Section 3.2: the backward pass at t uses the activations and weights of
+                              t - 2d). STORE: every saved tensor, in each of the 2d+1 ring slots. RECOMPUTE:
+                              only the module's input and output per slot plus a snapshot of the parameters
+                              that forward pass used; the other tensors are rebuilt, bit for bit, by a
+                              second forward pass right before the backward pass. Same results, less
+                              memory (dds_arena_bytes tells how much; the snapshots cost 4-6 bytes per
+                              parameter, slot and weight copy), one more forward per iteration in every
+                              module with d > 0. */
 } dds_spec;
 
 typedef struct dds_ctx dds_ctx;

@@ -22,6 +22,7 @@ DDS_SCHED_INTS = 8
 OPS = {"conv": 1, "linear": 2, "relu": 3, "maxpool2": 4, "gap": 5, "res_begin": 6, "res_add": 7,
        "softmax_ce": 8, "bn": 9}
 PRECISION = {"f32": 0, "bf16": 1}
+ACTIVATIONS = {"store": 0, "recompute": 1}  # dds_spec.activations
 
 EXPORTS = ["dds_schedule", "dds_step_size", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
            "dds_get_params", "dds_set_params", "dds_get_params_replica", "dds_consensus_error", "dds_step", "dds_get_loss", "dds_step_count",
@@ -40,7 +41,7 @@ class dds_spec(C.Structure):
                 ("bounds", C.POINTER(C.c_int32)), ("in_c", C.c_int32), ("in_h", C.c_int32),
                 ("in_w", C.c_int32), ("classes", C.c_int32), ("batch", C.c_int32),
                 ("precision", C.c_int32), ("lr", C.c_float), ("momentum", C.c_float),
-                ("mixing", C.POINTER(C.c_float))]
+                ("mixing", C.POINTER(C.c_float)), ("activations", C.c_int32)]
 
 
 class DdsError(RuntimeError):
@@ -115,7 +116,7 @@ def dds_schedule(K: int, delays: Optional[Sequence[int]], t: int) -> np.ndarray:
 class Spec:
     """Owns the ctypes arrays behind a dds_spec."""
 
-    def __init__(self, ops, bounds, in_shape, classes, batch, precision, lr, momentum, mixing=None):
+    def __init__(self, ops, bounds, in_shape, classes, batch, precision, lr, momentum, mixing=None, activations="store"):
         n = len(ops)
         self.layers = (dds_layer * n)()
         for i, op in enumerate(ops):
@@ -141,11 +142,11 @@ class Spec:
             flat = np.ascontiguousarray(np.asarray(mixing, dtype=np.float32)).ravel()
             self.mixing = (C.c_float * flat.size)(*flat.tolist())
         self.c = dds_spec(n, self.layers, self.bounds, in_shape[0], in_shape[1], in_shape[2], classes, batch,
-                          PRECISION[precision], lr, momentum, self.mixing)
+                          PRECISION[precision], lr, momentum, self.mixing, ACTIVATIONS[activations])
 
     @classmethod
-    def from_workload(cls, wl, mixing=None):
-        return cls(wl.ops, wl.bounds, wl.in_shape, wl.classes, wl.B, wl.precision, wl.lr, wl.momentum, mixing)
+    def from_workload(cls, wl, mixing=None, activations="store"):
+        return cls(wl.ops, wl.bounds, wl.in_shape, wl.classes, wl.B, wl.precision, wl.lr, wl.momentum, mixing, activations)
 
 
 def dds_arena_bytes(spec: Spec, K: int, W: int, delays=None) -> int:

@@ -60,7 +60,8 @@ struct Tensor {
   int kind = T_RING;
   bool relu_out = false;
   size_t bytes = 0;     // whole mini-batch of all replicas
-  size_t ring_off = 0;  // offset inside a ring slot (T_RING)
+  size_t ring_off = 0;  // offset inside a ring slot (T_RING), or inside the module's recompute area
+  bool recomputed = false;  // T_RING tensor that is not kept per slot: one copy, rebuilt before the backward pass
   bool has_bits = false;  // a sign plane (one bit per element, > 0) is kept beside the tensor in its ring slot
   size_t bits_off = 0;
   char* temp = nullptr; // T_TEMP storage
@@ -112,6 +113,14 @@ struct Module {
   std::vector<GradBuf> grads;
   size_t slot_bytes = 0;
   char* ring = nullptr;
+  // Recompute policy (modules with d > 0): a ring slot keeps only what other iterations or modules read (the
+  // module's output with its sign plane; module 0's ingested input); every other saved tensor and the batch-norm
+  // statistics have one copy in `area`, which the forward pass fills for mini-batch f and a second forward pass,
+  // run on the ring's input with the parameter snapshot of that slot, refills for mini-batch b before the backward.
+  bool recompute = false;
+  char* area = nullptr;
+  float* snap_master = nullptr;  // [R][copies][n_master] fp32 parameters as the forward of that slot saw them
+  char* snap_work = nullptr;     // the same for the compute-precision copy (bf16 path)
   double* bn_scratch = nullptr;  // per-split sums of the batch-normalisation kernels (largest node of the module)
   double* bn_totals = nullptr;   // dbeta / dgamma per data-group and channel of the node being back-propagated
   long long n_master = 0;  // floats per weight copy
@@ -166,6 +175,7 @@ struct dds_ctx {
   // True while the done events of the previous iteration describe everything a module program depends on:
   // cleared by every call that touches module state from the caller's stream outside dds_step.
   bool chained = false;
+  bool recompute = false;  // activation policy of the spec (applies to modules with d > 0)
   hipStream_t last_stream = nullptr;  // stream of the previous dds_step
   hipEvent_t step_end = nullptr;      // recorded on it after that step's joins
   std::vector<hipStream_t> pool;  // internal streams; module k0 runs on the caller's stream if k0 % (pool+1) == 0
@@ -491,21 +501,28 @@ int layout(dds_ctx& c, Arena& A) {
   for (int k0 = 0; k0 < c.K; ++k0) {
     Module& m = c.mods[k0];
     // ring: R slots of every saved tensor
-    size_t off = 0;
-    for (Tensor& t : m.tensors)
-      if (t.kind == T_RING) {
-        t.ring_off = off;
-        off = align_up(off + t.bytes, 256);
-        if (t.has_bits) { t.bits_off = off; off = align_up(off + (size_t)c.N * t.H * t.W * t.Cpad / 8, 256); }
-      }
+    size_t off = 0, aoff = 0;
+    m.recompute = c.recompute && m.d > 0;
+    for (size_t ti = 0; ti < m.tensors.size(); ++ti) {
+      Tensor& t = m.tensors[ti];
+      if (t.kind != T_RING) continue;
+      t.recomputed = m.recompute && (int)ti != m.out_tensor && !(k0 == 0 && ti == 0);
+      size_t& o = t.recomputed ? aoff : off;
+      t.ring_off = o;
+      o = align_up(o + t.bytes, 256);
+      if (t.has_bits) { t.bits_off = o; o = align_up(o + (size_t)c.N * t.H * t.W * t.Cpad / 8, 256); }
+    }
     // batch normalisation: what the backward of a mini-batch needs from its forward (mean, rstd, gamma
     // per data-group and channel) lives in the ring slot too; the row splits are fixed here
     size_t bn_scratch_bytes = 0, bn_totals_bytes = 0;
     for (Node& nd : m.nodes) {
       if (nd.kind != N_BN) continue;
       const Tensor& tb = m.tensors[nd.out];
-      nd.stats_off = off;
-      off = align_up(off + (size_t)c.W * 3 * tb.Cpad * 4, 256);
+      {
+        size_t& o = m.recompute ? aoff : off;
+        nd.stats_off = o;
+        o = align_up(o + (size_t)c.W * 3 * tb.Cpad * 4, 256);
+      }
       const long long rows_per_rep = (long long)c.B * tb.H * tb.W;
       // about 32 KiB of the tensor per workgroup, at most 512 splits per data-group
       long long ns = rows_per_rep * tb.Cpad * es / 32768;
@@ -519,6 +536,7 @@ int layout(dds_ctx& c, Arena& A) {
     }
     m.slot_bytes = off;
     m.ring = A.take(m.slot_bytes * m.R);
+    if (m.recompute) m.area = A.take(aoff);
     if (bn_scratch_bytes) { m.bn_scratch = (double*)A.take(bn_scratch_bytes); m.bn_totals = (double*)A.take(bn_totals_bytes); }
     for (Tensor& t : m.tensors)
       if (t.kind == T_TEMP) t.temp = A.take(t.bytes);
@@ -526,6 +544,10 @@ int layout(dds_ctx& c, Arena& A) {
     m.master = (float*)A.take((size_t)m.n_master * 4 * c.copies);
     if (c.mu != 0.f) m.momentum = (float*)A.take((size_t)m.n_master * 4 * c.copies);
     if (c.dt == DT_BF16) m.work = A.take((size_t)m.n_master * es * c.copies);
+    if (m.recompute) {
+      m.snap_master = (float*)A.take((size_t)m.n_master * 4 * c.copies * m.R);
+      if (c.dt == DT_BF16) m.snap_work = A.take((size_t)m.n_master * es * c.copies * m.R);
+    }
     for (Node& nd : m.nodes) {
       if (nd.kind == N_BN) {  // one parameter-gradient row per data-group
         ParamLayer& L = m.layers[nd.layer];
@@ -608,6 +630,8 @@ int build(dds_ctx& c, const dds_spec* sp, int K, int W, const int* delays) {
   c.in_w = sp->in_w;
   c.lr = sp->lr;
   c.mu = sp->momentum;
+  if (sp->activations != DDS_ACT_STORE && sp->activations != DDS_ACT_RECOMPUTE) return fail(DDS_EINVAL, "unknown activation policy");
+  c.recompute = sp->activations == DDS_ACT_RECOMPUTE;
   if (sp->mixing) {
     // Section 2.3: P symmetric, doubly stochastic, entries in [0,1]
     for (int i = 0; i < W; ++i) {
@@ -664,7 +688,7 @@ struct Exec {
   char* tensor_ptr(int ti, int slot) const {
     const Tensor& t = m.tensors[ti];
     if (t.kind == T_TEMP) return t.temp;
-    if (t.kind == T_RING) return m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
+    if (t.kind == T_RING) return t.recomputed ? m.area + t.ring_off : m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
     return nullptr;  // external handled by caller
   }
 };
@@ -679,7 +703,10 @@ char* input_ptr(dds_ctx& c, int k0, int64_t batch) {
 // sign plane of a tensor in the given ring slot (null if it has none)
 char* bits_ptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
   const Tensor& t = m.tensors[ti];
-  if (t.kind == T_RING) return t.has_bits ? m.ring + (size_t)slot * m.slot_bytes + t.bits_off : nullptr;
+  if (t.kind == T_RING) {
+    if (!t.has_bits) return nullptr;
+    return t.recomputed ? m.area + t.bits_off : m.ring + (size_t)slot * m.slot_bytes + t.bits_off;
+  }
   if (t.kind == T_EXTERNAL) {
     Module& up = c.mods[m.k0 - 1];
     const Tensor& ut = up.tensors[up.out_tensor];
@@ -692,7 +719,7 @@ char* bits_ptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
 char* tptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
   const Tensor& t = m.tensors[ti];
   if (t.kind == T_TEMP) return t.temp;
-  if (t.kind == T_RING) return m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
+  if (t.kind == T_RING) return t.recomputed ? m.area + t.ring_off : m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
   return input_ptr(c, m.k0, batch);
 }
 
@@ -719,24 +746,26 @@ hipEvent_t prof_event(dds_ctx& c) {
 // cls: 0 forward, 1 dgrad, 2 wgrad; + 3 once the launch reports the asynchronous kernel family
 struct ProfScope {
   dds_ctx& c; hipStream_t s; int cls; double flops; hipEvent_t a = nullptr;
-  ProfScope(dds_ctx& c_, hipStream_t s_, int cls_, double flops_) : c(c_), s(s_), cls(cls_), flops(flops_) {
-    if (c.profiling) { a = prof_event(c); (void)hipEventRecord(a, s); }
+  bool on;
+  ProfScope(dds_ctx& c_, hipStream_t s_, int cls_, double flops_, bool enabled = true)
+      : c(c_), s(s_), cls(cls_), flops(flops_), on(c_.profiling && enabled) {
+    if (on) { a = prof_event(c); (void)hipEventRecord(a, s); }
   }
   ~ProfScope() {
-    if (c.profiling) { hipEvent_t b = prof_event(c); (void)hipEventRecord(b, s); c.prof_pending.push_back({cls, flops, a, b}); }
+    if (on) { hipEvent_t b = prof_event(c); (void)hipEventRecord(b, s); c.prof_pending.push_back({cls, flops, a, b}); }
   }
 };
 
 // Fields of a batch-normalisation launch that forward and backward share; slot = ring slot of the mini-batch.
-BnParams bn_params(dds_ctx& c, Module& m, const Node& nd, int slot) {
+BnParams bn_params(dds_ctx& c, Module& m, const Node& nd, int slot, const float* master) {
   const ParamLayer& L = m.layers[nd.layer];
   const Tensor& to = m.tensors[nd.out];
   BnParams p{};
-  p.gamma = m.master + L.off;
-  p.beta = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
+  p.gamma = (float*)master + L.off;
+  p.beta = (float*)master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
   p.rep_stride = c.gossip ? m.n_master : 0;
   p.gstride = L.Cinpad;
-  p.stats = (float*)(m.ring + (size_t)slot * m.slot_bytes + nd.stats_off);
+  p.stats = (float*)(m.recompute ? m.area + nd.stats_off : m.ring + (size_t)slot * m.slot_bytes + nd.stats_off);
   p.scratch = m.bn_scratch;
   p.totals = m.bn_totals;
   p.partial = L.partial;
@@ -753,9 +782,14 @@ BnParams bn_params(dds_ctx& c, Module& m, const Node& nd, int slot) {
   return p;
 }
 
-void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
-  const int slot = (int)(t % m.R);
+// Forward pass of mini-batch f through the tensors of ring slot `slot`. snap < 0: with the current parameters (the
+// pass of iteration t = f + k0). snap >= 0: the same pass again with the parameter snapshot of that slot, which
+// rebuilds the tensors the recompute policy does not keep (the kernels are deterministic: identical bits).
+void run_forward(dds_ctx& c, Module& m, int slot, int64_t f, hipStream_t s, int snap = -1) {
   const int es = dtype_size(c.dt);
+  const size_t snap_off = snap >= 0 ? (size_t)snap * c.copies * m.n_master : 0;
+  const float* master = snap >= 0 ? m.snap_master + snap_off : m.master;
+  const char* work = snap >= 0 ? (m.snap_work ? m.snap_work + snap_off * es : nullptr) : m.work;
   for (const Node& nd : m.nodes) {
     if (nd.kind == N_CE) continue;
     const Tensor& ti = m.tensors[nd.in];
@@ -767,9 +801,9 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
         const ParamLayer& L = m.layers[nd.layer];
         ConvParams p{};
         p.x = x;
-        p.w = c.dt == DT_BF16 ? (const void*)(m.work + (size_t)L.off * es) : (const void*)(m.master + L.off);
+        p.w = c.dt == DT_BF16 ? (const void*)(work + (size_t)L.off * es) : (const void*)(master + L.off);
         p.y = y;
-        p.bias = m.master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
+        p.bias = master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
         p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
         p.mask = nullptr;
         p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
@@ -790,13 +824,14 @@ void run_forward(dds_ctx& c, Module& m, int64_t t, int64_t f, hipStream_t s) {
         p.out_f32 = nd.out_f32;
         p.dgrad = 0;
         {
-          ProfScope ps(c, s, 0, 2.0 * p.M * L.Cout * L.Cin * L.RS);
+          // the per-class launch timings cover each launch once: the repeated pass is the same launches again
+          ProfScope ps(c, s, 0, 2.0 * p.M * L.Cout * L.Cin * L.RS, snap < 0);
           ps.cls += 3 * launch_conv(c.dt, p, s);
         }
         break;
       }
       case N_BN: {
-        BnParams p = bn_params(c, m, nd, slot);
+        BnParams p = bn_params(c, m, nd, slot, master);
         p.x = x;
         p.y = y;
         p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
@@ -893,7 +928,7 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
         break;
       }
       case N_BN: {
-        BnParams p = bn_params(c, m, nd, slot);
+        BnParams p = bn_params(c, m, nd, slot, m.master);
         p.x = x;
         p.dy = gout;
         p.dx = gin;
@@ -915,6 +950,18 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
         break;
     }
   }
+}
+
+// Recompute policy: the parameters the next forward pass will use, copied into snapshot slot `slot`.
+hipError_t snapshot_params(dds_ctx& c, Module& m, int slot, hipStream_t s) {
+  const size_t n = (size_t)m.n_master * c.copies;
+  hipError_t e = hipMemcpyAsync(m.snap_master + (size_t)slot * n, m.master, n * 4, hipMemcpyDeviceToDevice, s);
+  if (e == hipSuccess && m.snap_work) {
+    const size_t es = dtype_size(c.dt);
+    e = hipMemcpyAsync(m.snap_work + (size_t)slot * n * es, m.work, n * es, hipMemcpyDeviceToDevice, s);
+  }
+  c.launches += m.snap_work ? 2 : 1;
+  return e;
 }
 
 int upload_tables(dds_ctx& c) {
@@ -1131,8 +1178,10 @@ static int params_io(dds_ctx* c, int module, int replica, float* buf, size_t n_f
       HIP_TRY(hipMemcpyAsync(m.master + (size_t)r * m.n_master, m.master, (size_t)m.n_master * 4, hipMemcpyDeviceToDevice, s));
     if (m.momentum) launch_fill_zero(m.momentum, (size_t)m.n_master * 4 * c->copies, s);
     launch_recast(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update * c->copies, s);
-    for (int slot = 0; slot < m.R; ++slot)
+    for (int slot = 0; slot < m.R; ++slot) {
       launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, slot, s);
+      if (m.recompute) HIP_TRY(snapshot_params(*c, m, slot, s));
+    }
   }
   HIP_TRY(hipGetLastError());
   return DDS_OK;
@@ -1220,12 +1269,13 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
     }
     const int64_t f = t - k0, b = t - k0 - 2 * m.d;
     const bool last = k0 == c->K - 1;
-    if (f >= 0) run_forward(*c, m, t, f, s);
-    if (last) {
+    const int bslot = (int)(((t - 2 * m.d) % m.R + m.R) % m.R);
+    if (f >= 0) run_forward(*c, m, (int)(t % m.R), f, s);
+    if (last && f >= 0) {
       const Node& ce = m.nodes.back();
       const Tensor& lt = m.tensors[ce.in];
       const int ldg = lt.Cpad;
-      if (f >= 0) {
+      {
         const float* logits = (const float*)tptr(*c, m, ce.in, (int)(t % m.R), f);
         const int32_t* lab = c->labels + (size_t)(f % c->label_depth) * c->N;
         void* dl = (b == f) ? gptr(*c, m, ce.gin, t) : nullptr;
@@ -1233,9 +1283,14 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
         ++c->launches;
         c->have_loss = true;
       }
+    }
+    if (m.recompute && b >= 0) run_forward(*c, m, bslot, b, s, bslot);
+    if (last) {
+      const Node& ce = m.nodes.back();
+      const Tensor& lt = m.tensors[ce.in];
+      const int ldg = lt.Cpad;
       if (b >= 0 && b != f) {
-        const int slot = (int)(((t - 2 * m.d) % m.R + m.R) % m.R);
-        const float* logits = (const float*)tptr(*c, m, ce.in, slot, b);
+        const float* logits = (const float*)tptr(*c, m, ce.in, bslot, b);
         const int32_t* lab = c->labels + (size_t)(b % c->label_depth) * c->N;
         launch_softmax_ce(c->dt, logits, lab, gptr(*c, m, ce.gin, t), nullptr, c->W, c->B, c->classes, lt.Cpad, ldg, s);
         ++c->launches;
@@ -1252,6 +1307,7 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
       }
       launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, (int)((t + 1) % m.R), s);
       c->launches += 2;
+      if (m.recompute) HIP_TRY(snapshot_params(*c, m, (int)((t + 1) % m.R), s));
     }
     if (multi) HIP_TRY(hipEventRecord(m.done[t & 1], s));
   }

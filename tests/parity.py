@@ -7,10 +7,10 @@ import numpy as np
 from dds_inputs import make_batch, make_params, param_shapes
 
 
-def run_hip(wl, seed, T, delays=None, every_step=False, lr_schedule=None):
+def run_hip(wl, seed, T, delays=None, every_step=False, lr_schedule=None, activations="store"):
     import torch
     import paper_2509_05679_amd as P
-    spec = P.Spec.from_workload(wl)
+    spec = P.Spec.from_workload(wl, activations=activations)
     tr = P.Trainer(spec, wl.W, delays)
     init = make_params(wl, seed)
     for k0 in range(wl.K):

@@ -62,6 +62,25 @@ def test_arena_sizing_of_the_benchmark_configs(name):
     assert P.dds_arena_bytes(P.Spec.from_workload(half), wl.K, wl.W) < n
 
 
+def test_recompute_policy_shrinks_the_arena_of_delayed_modules_only():
+    """Recompute keeps one input and one output per ring slot instead of every saved tensor; a net whose only
+    module has d = 0 keeps nothing across iterations, so the policy changes nothing there."""
+    for name in ("cfg1_cnn", "cfg2_resnet18", "cfg3_resnet56", "cfg4_resnet34w"):
+        wl = workload(name)
+        store = P.dds_arena_bytes(P.Spec.from_workload(wl), wl.K, wl.W)
+        rec = P.dds_arena_bytes(P.Spec.from_workload(wl, activations="recompute"), wl.K, wl.W)
+        assert rec < 0.7 * store, (name, store, rec)
+    from dds_inputs.configs import tiny_resnet
+    one = tiny_resnet(K=1)
+    assert P.dds_arena_bytes(P.Spec.from_workload(one), 1, one.W) == \
+        P.dds_arena_bytes(P.Spec.from_workload(one, activations="recompute"), 1, one.W)
+    bad = P.Spec.from_workload(one)
+    bad.c.activations = 7
+    with pytest.raises(P.DdsError) as e:
+        P.dds_arena_bytes(bad, 1, one.W)
+    assert e.value.code == P.DDS_EINVAL
+
+
 def test_paper_experiment_workloads_are_resnet20():
     from dds_inputs.configs import PAPER_WORKLOAD_NAMES
     assert set(PAPER_WORKLOAD_NAMES) == {"paper_r20_S1K1", "paper_r20_S1K2", "paper_r20_S4K1", "paper_r20_S4K2"}
