@@ -94,3 +94,52 @@ def test_cfg2_bn_full_size_first_update():
     # oracle's for a fraction of a percent of the elements (see test_gpu_batchnorm.py), which moves upstream
     # gradients by up to ~16 % here; per tensor, the update guard or the stated bar relative to the parameter
     _first_update(workload("cfg2_resnet18_bn"), seed=5, mixing=None, update_tol=2.5e-1, rel_tol=2e-2)
+
+
+def test_cfg2_full_size_long_run_properties():
+    """Properties that hold at any size, at the shapes and in the launch configuration bench.py times (steps
+    enqueued back to back on resident batches, so the module programs run ahead of each other): a module's
+    weights are bit-exactly the initial ones until its first gradient arrives at iteration 2(K-1)-k0
+    (Section 3.2: the gradient is defined as zero before that) and differ right after it; everything stays
+    finite; and the stale-gradient iteration still descends: cycling over two fixed mini-batches per
+    data-group at the configuration's step size, the loss (ln 10 at initialisation) falls steadily, by more than
+    0.2 over 300 iterations."""
+    import torch
+    import paper_2509_05679_amd as P
+    wl = workload("cfg2_resnet18")
+    K, seed, pool = wl.K, 17, 2
+    tr = P.Trainer(P.Spec.from_workload(wl), wl.W)
+    init = make_params(wl, seed)
+    flat = [np.concatenate([p.ravel() for p in m]) for m in init]
+    for k0 in range(K):
+        tr.dds_set_params(k0, init[k0])
+    xs = [[torch.from_numpy(make_batch(wl, seed, t, s)[0]).cuda() for s in range(wl.W)] for t in range(pool)]
+    ys = [[torch.from_numpy(make_batch(wl, seed, t, s)[1]).cuda() for s in range(wl.W)] for t in range(pool)]
+    first = [2 * (K - 1) - k0 for k0 in range(K)]  # iteration of module k0's first update
+    t = 0
+
+    def advance(to):
+        nonlocal t
+        while t < to:
+            tr.dds_step(xs[t % pool], ys[t % pool])
+            t += 1
+
+    for k0 in reversed(range(K)):  # first[] increases towards module 0
+        advance(first[k0])        # iterations 0 .. first-1 done: no gradient yet
+        assert np.array_equal(tr.dds_get_params(k0), flat[k0]), k0
+        advance(first[k0] + 1)
+        assert not np.array_equal(tr.dds_get_params(k0), flat[k0]), k0
+    advance(K)
+    loss0 = None
+    losses = []
+    while t < 300:
+        advance(t + 25)
+        losses.append(tr.dds_get_loss())
+        loss0 = losses[0] if loss0 is None else loss0
+    params = [tr.dds_get_params(k0) for k0 in range(K)]
+    tr.close()
+    print(f"[full] cfg2 long run: losses {['%.3f' % v for v in losses]}", flush=True)
+    assert all(np.isfinite(p).all() for p in params)
+    assert all(np.isfinite(losses))
+    assert losses[-1] < losses[0] - 0.2, losses
+    assert all(b < a + 0.01 for a, b in zip(losses, losses[1:])), losses
