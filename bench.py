@@ -80,7 +80,7 @@ def cpu_baseline(wl, seconds_budget=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg2_resnet18")
     ap.add_argument("--batch", type=int, default=None, help="override per-replica batch (debug only)")
@@ -143,6 +143,16 @@ def main():
     hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1)
     ms_per_step = ms.value / args.steps
     loss = tr.dds_get_loss()
+    # four more regions of the same length, for the spread only: `value` is the region above
+    runs = [ms_per_step]
+    for r in range(4):
+        hip.hipEventRecord(e0, sp)
+        for t in range(args.steps):
+            tr.dds_step(xs[(warmup + t) % pool], ys[(warmup + t) % pool])
+        hip.hipEventRecord(e1, sp)
+        hip.hipEventSynchronize(e1)
+        hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1)
+        runs.append(ms.value / args.steps)
     samples = wl.W * wl.B
     flops = tr.dds_gemm_flops_per_step()
     launches = tr.dds_launches_last_step()
@@ -204,6 +214,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: K={wl.K} modules, W={wl.W} replicas x batch {wl.B}, {wl.precision}",
                    "launches_per_step": launches, "wall_ms_per_step": wall * 1e3 / args.steps,
+                   "ms_per_step_of_5_regions": [round(v, 4) for v in runs], "median_ms_per_step": sorted(runs)[2],
                    "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30, "mixing": args.mixing, "activations": args.activations,
                    "consensus_error": tr.dds_consensus_error() if mixing is not None else 0.0},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
