@@ -53,7 +53,16 @@ def schedule(t: int, K: int, d: Optional[Sequence[int]] = None) -> List[dict]:
     fwd_slot = t mod R is written by the forward, bwd_slot = (t-2d) mod R is read
     by the backward; err_depth / err_write / err_read index the error-gradient
     mailbox between module k0+1 (writer) and k0 (reader); label_slot indexes the
-    queue (depth K + 2 d[K-1]) of targets travelling to the last module."""
+    queue (depth K + 2 d[K-1]) of targets travelling to the last module.
+    Further integers an implementation with shared storage needs, all consequences of
+    the above: in_fwd_slot / in_bwd_slot = the slot of module k0-1's ring that holds the
+    output module k0-1 produced for mini-batch f / b (it forwarded that batch one
+    iteration before module k0 did, i.e. at f+k0-1 / b+k0-1), -1 for module 0;
+    snap_write = (t+1) mod R, where the weights after this iteration's update are
+    snapshotted (they are the ones the forward of iteration t+1 uses);
+    label_write = t mod queue depth for module 0 (targets of the batch sampled now);
+    label_bwd_slot = b mod queue depth for the last module (targets of the batch whose
+    loss gradient starts this iteration's backward), -1 otherwise."""
     d = paper_delays(K) if d is None else list(d)
     out = []
     for k0 in range(K):
@@ -74,7 +83,17 @@ def schedule(t: int, K: int, d: Optional[Sequence[int]] = None) -> List[dict]:
             rec["err_write"] = t % (lag_up + 1)
         else:
             rec["err_write"] = -1
-        rec["label_slot"] = (f % (K + 2 * d[K - 1])) if (k0 == K - 1 and f >= 0) else -1
+        depth = K + 2 * d[K - 1]
+        rec["label_slot"] = (f % depth) if (k0 == K - 1 and f >= 0) else -1
+        if k0 > 0:
+            R_up = 2 * d[k0 - 1] + 1
+            rec["in_fwd_slot"] = ((f + k0 - 1) % R_up) if f >= 0 else -1
+            rec["in_bwd_slot"] = ((b + k0 - 1) % R_up) if b >= 0 else -1
+        else:
+            rec["in_fwd_slot"] = rec["in_bwd_slot"] = -1
+        rec["snap_write"] = (t + 1) % R
+        rec["label_write"] = (t % depth) if k0 == 0 else -1
+        rec["label_bwd_slot"] = (b % depth) if (k0 == K - 1 and b >= 0) else -1
         out.append(rec)
     return out
 
@@ -120,15 +139,24 @@ def mean_matrix(S: int) -> torch.Tensor:
 
 
 def consensus_error(weights) -> float:
-    """max over layers l and data-groups s of || w_{s,l} - mean_s w_{s,l} ||
-    (the disagreement measure of the experiment section). weights[s][k0][j]."""
+    """Disagreement measure delta(t) of the experiment section: the maximum over layers l and
+    data-groups s of || w_{s,l} - (1/S) sum_r w_{r,l} ||_2, where w_{s,l} is data-group s's
+    weight vector of layer l in the sense of Section 2.1 (w_l in R^{d_l}: ALL parameters of
+    the layer, i.e. weight and bias -- gamma and beta for a normalisation -- as one vector).
+    weights[s][k0][j]: the flat canonical list of module k0, in which every layer
+    contributes two consecutive tensors (weight, bias)."""
     S = len(weights)
     worst = 0.0
     for k0 in range(len(weights[0])):
-        for j in range(len(weights[0][k0])):
-            avg = sum(weights[s][k0][j] for s in range(S)) / S
-            for s in range(S):
-                worst = max(worst, float(torch.linalg.vector_norm(weights[s][k0][j] - avg)))
+        n = len(weights[0][k0])
+        assert n % 2 == 0
+        for j in range(0, n, 2):
+            sq = [0.0] * S
+            for part in (j, j + 1):
+                avg = sum(weights[s][k0][part] for s in range(S)) / S
+                for s in range(S):
+                    sq[s] += float(((weights[s][k0][part] - avg) ** 2).sum())
+            worst = max(worst, max(sq) ** 0.5)
     return worst
 
 
@@ -138,7 +166,10 @@ class Pipeline:
     iteration left in the mailboxes; nothing computed in iteration t is consumed
     before iteration t+1 except by the agent that computed it."""
 
-    def __init__(self, ops, bounds, S, init_params, lr, momentum=0.0, delays=None, P=None):
+    def __init__(self, ops, bounds, S, init_params, lr, momentum=0.0, delays=None, P=None, q=None):
+        # q: optional storage rounding handed to every forward / backward pass (diagnostic mode of
+        # oracle.network; None = exact fp64, the contract)
+        self.q = q
         self.ops = ops
         self.bounds = list(bounds)
         self.K = len(bounds) - 1
@@ -192,7 +223,7 @@ class Pipeline:
                 if f >= 0:
                     hin = torch.as_tensor(x, dtype=DT) if k0 == 0 else self.act_mail[s][k0]
                     out, saved, loss = N.forward(ops, self.w[s][k0], hin,
-                                                 self.labels[s][f] if last else None)
+                                                 self.labels[s][f] if last else None, q=self.q)
                     self.inflight[s][k0][f] = (saved, self.w[s][k0], out if last else None)
                     if last:
                         losses.append(loss)
@@ -203,7 +234,7 @@ class Pipeline:
                 if b >= 0:
                     saved, w_old, dlogits = self.inflight[s][k0].pop(b)
                     dout = dlogits if last else self.err_mail[s][k0].pop(b)
-                    dx, g = N.backward(ops, w_old, saved, dout, need_dx=(k0 > 0))
+                    dx, g = N.backward(ops, w_old, saved, dout, need_dx=(k0 > 0), q=self.q)
                     grads[s][k0] = g
                     if k0 > 0:
                         new_err.append((s, k0 - 1, b, dx))
@@ -240,10 +271,11 @@ class Pipeline:
 
 
 # ----------------------------------------------------------------------------- O-def
-def definition_gradient(ops, bounds, skewed_weights, x, y):
+def definition_gradient(ops, bounds, skewed_weights, x, y, q=None):
     """Ordinary (locked) backpropagation of the whole network on one mini-batch at
     the weight vector `skewed_weights` (list over modules of param lists).
-    Returns grads[k0] aligned with skewed_weights[k0] and the loss."""
+    Returns grads[k0] aligned with skewed_weights[k0] and the loss.
+    q: optional storage rounding (diagnostic mode of oracle.network)."""
     K = len(bounds) - 1
     h = torch.as_tensor(x, dtype=DT)
     saved_all = []
@@ -251,7 +283,7 @@ def definition_gradient(ops, bounds, skewed_weights, x, y):
     for k0 in range(K):
         mops = ops[bounds[k0]:bounds[k0 + 1]]
         h, saved, l = N.forward(mops, skewed_weights[k0], h,
-                                torch.as_tensor(y, dtype=torch.int64) if k0 == K - 1 else None)
+                                torch.as_tensor(y, dtype=torch.int64) if k0 == K - 1 else None, q=q)
         saved_all.append(saved)
         if l is not None:
             loss = l
@@ -259,7 +291,7 @@ def definition_gradient(ops, bounds, skewed_weights, x, y):
     grads = [None] * K
     for k0 in range(K - 1, -1, -1):
         mops = ops[bounds[k0]:bounds[k0 + 1]]
-        d, grads[k0] = N.backward(mops, skewed_weights[k0], saved_all[k0], d, need_dx=(k0 > 0))
+        d, grads[k0] = N.backward(mops, skewed_weights[k0], saved_all[k0], d, need_dx=(k0 > 0), q=q)
     return grads, loss
 
 

@@ -158,3 +158,11 @@ def softmax_ce_fwd(logits, labels):
     p = torch.exp(logp)
     p[idx, lab] -= 1.0
     return loss, (p / n).reshape(logits.shape)
+
+
+def round_bf16(x):
+    """Storage rounding of the diagnostic mode (oracle.network): the value as an fp32 number
+    rounded to bfloat16 (8 significand bits: the upper 16 bits of the fp32 pattern) to
+    nearest, ties to even, returned in fp64. The two conversions are the array library's;
+    tests/test_oracle_layers.py pins them to the bit-pattern definition."""
+    return x.to(torch.float32).to(torch.bfloat16).to(DT)

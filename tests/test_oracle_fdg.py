@@ -80,16 +80,25 @@ def test_ring_and_mailbox_slots_never_clobber_live_data(K, d):
     rings = [dict() for _ in range(K)]
     errs = [dict() for _ in range(K)]
     labels = {}
+    snaps = [{j: 0 for j in range(2 * d[k0] + 1)} for k0 in range(K)]  # every slot starts with the initial weights w(0)
     for t in range(80):
         sch = fdg.schedule(t, K, d)
-        labels[t % (K + 2 * d[K - 1])] = t
+        labels[sch[0]["label_write"]] = t
         # reads happen against the state left by earlier iterations (plus own forward)
         for rec in sch:
             k0 = rec["k0"]
             if rec["f"] >= 0:
+                if k0 > 0:  # the input is still in the ring of the module below
+                    assert rings[k0 - 1][rec["in_fwd_slot"]] == rec["f"]
                 rings[k0][rec["fwd_slot"]] = rec["f"]
             if k0 == K - 1 and rec["f"] >= 0:
                 assert labels[rec["label_slot"]] == rec["f"]
+            if k0 == K - 1 and rec["b"] >= 0:
+                assert labels[rec["label_bwd_slot"]] == rec["b"]
+            if rec["b"] >= 0:
+                # the snapshot in the backward slot is the weight version the forward of batch b used:
+                # w(b + k0) = w(t - 2 d), Section 3.2's w(t - 2K + 2k) under the paper's delays
+                assert snaps[k0][rec["bwd_slot"]] == rec["b"] + k0 == t - 2 * d[k0]
         pending = []
         for rec in sch:
             k0 = rec["k0"]
@@ -101,11 +110,11 @@ def test_ring_and_mailbox_slots_never_clobber_live_data(K, d):
                     pending.append((k0 - 1, rec["err_write"], rec["b"]))
                 # the module below reads this module's input from the ring of k0-1
                 if k0 > 0:
-                    up = sch[k0 - 1]
-                    slot = (rec["b"] + (k0 - 1)) % up["ring_depth"]
-                    assert rings[k0 - 1][slot] == rec["b"]
+                    assert rings[k0 - 1][rec["in_bwd_slot"]] == rec["b"]
         for k0, slot, b in pending:
             errs[k0][slot] = b
+        for rec in sch:  # weights after this iteration = version t+1
+            snaps[rec["k0"]][rec["snap_write"]] = t + 1
 
 
 def test_delay_causality_is_enforced():
@@ -277,6 +286,27 @@ def test_gossip_matrix_properties():
         assert float(gamma) < 1.0
     assert torch.allclose(fdg.gossip_matrix(4, [(i, j) for i in range(4) for j in range(i + 1, 4)], 0.25),
                           fdg.mean_matrix(4))
+
+
+def test_disagreement_measure_on_hand_worked_cases():
+    """delta of the experiment section, written out by hand on integer weights: the maximum over layers
+    and data-groups of the Euclidean distance between a data-group's layer weight vector (weight AND bias,
+    Section 2.1's w_l) and the average of that vector over the data-groups."""
+    t = lambda v: torch.tensor(v, dtype=DT)
+    # two data-groups, one module with two layers
+    g0 = [[t([[1, 2], [3, 4]]), t([0, 2]), t([[5]]), t([1])]]
+    g1 = [[t([[3, 2], [3, 0]]), t([2, 2]), t([[1]]), t([1])]]
+    # layer A: mean weight [[2,2],[3,2]], mean bias [1,2]; deviations +-([[1,0],[0,2]], [1,0]): norm sqrt(1+4+1)
+    # layer B: mean 3 / 1; deviations +-2 / 0: norm 2
+    assert abs(fdg.consensus_error([g0, g1]) - 6 ** 0.5) < 1e-15
+    # three data-groups, two modules; the largest deviation sits in module 1 and in the bias as much as the weight
+    a = [[t([0, 0]), t([0])], [t([0, 0]), t([0])]]
+    b = [[t([0, 0]), t([0])], [t([3, 0]), t([0])]]
+    c = [[t([0, 0]), t([0])], [t([0, 3]), t([3])]]
+    # module 1: mean weight [1,1], mean bias 1; deviations a: ([-1,-1],-1) -> sqrt 3; b: ([2,-1],-1) -> sqrt 6;
+    # c: ([-1,2],2) -> 3. Per tensor the maximum would be sqrt 5, without the root 9, with a mean over groups ~2.4.
+    assert abs(fdg.consensus_error([a, b, c]) - 3.0) < 1e-15
+    assert fdg.consensus_error([a, a, a]) == 0.0
 
 
 def test_exact_mean_keeps_replicas_identical():

@@ -224,3 +224,24 @@ def test_batchnorm_backward_autograd_finite_differences_and_orthogonality():
         e[c] = h
         assert abs((f(x, gamma + e, beta) - f(x, gamma - e, beta)) / (2 * h) - float(dgamma[c])) < 1e-6
         assert abs((f(x, gamma, beta + e) - f(x, gamma, beta - e)) / (2 * h) - float(dbeta[c])) < 1e-6
+
+
+def test_round_bf16_is_round_to_nearest_even_on_the_upper_sixteen_bits():
+    """Pins of the storage rounding used by the oracle's diagnostic mode: hand-worked values (bf16 keeps
+    8 significand bits, so the spacing in [1, 2) is 2^-7 and a tie sits at odd multiples of 2^-8) and the
+    bit-pattern definition on random values of every magnitude."""
+    r = lambda v: float(L.round_bf16(torch.tensor([v], dtype=DT))[0])
+    assert r(1.0) == 1.0
+    assert r(1 + 2.0 ** -8) == 1.0                      # tie -> even (significand ...0)
+    assert r(1 + 3 * 2.0 ** -8) == 1 + 2.0 ** -6        # tie -> even (1 + 2/128 -> significand ...10)
+    assert r(1 + 2.0 ** -8 + 2.0 ** -20) == 1 + 2.0 ** -7   # just above the tie -> up
+    assert r(-1 - 2.0 ** -8) == -1.0
+    assert r(0.0) == 0.0 and r(3.0) == 3.0 and r(-0.15625) == -0.15625
+    assert r(1 + 2.0 ** -8 + 2.0 ** -40) == 1.0         # the fp32 step comes first: 2^-40 is lost, then the tie goes to even
+    g = torch.Generator().manual_seed(9)
+    x = torch.randn(200000, dtype=DT, generator=g) * torch.exp(8 * torch.randn(200000, dtype=DT, generator=g))
+    bits = x.to(torch.float32).view(torch.int32).to(torch.int64) & 0xFFFFFFFF
+    want = ((bits + 0x7FFF + ((bits >> 16) & 1)) >> 16) << 16
+    want = torch.where(want >= 2 ** 31, want - 2 ** 32, want).to(torch.int32).view(torch.float32).to(DT)
+    assert torch.equal(L.round_bf16(x), want)
+    assert torch.equal(L.round_bf16(L.round_bf16(x)), L.round_bf16(x))   # idempotent

@@ -177,3 +177,75 @@ def test_bf16_quantised_normalisation_input_moves_upstream_gradients_by_percents
     assert 5e-3 < conv2_w < 1e-1 and 5e-3 < conv0_w < 1e-1   # percents
     assert gamma < 5e-3 and beta < 1e-2                         # tenths of a percent
     assert conv2_w > 5 * gamma
+
+
+def test_storage_rounding_mode_rounds_exactly_at_the_documented_points():
+    """The diagnostic mode of oracle.network with a recording q: the sequence of rounded tensors (by
+    shape) on a residual block with a projection shortcut, and q = identity leaves every result bit-equal
+    to the exact mode."""
+    from dds_inputs.configs import Workload, _conv, _linear, _relu
+    c = 4
+    ops = [_conv(3, c), _relu(),
+           {"op": "res_begin"}, _conv(c, 2 * c, stride=2), _relu(), _conv(2 * c, 2 * c),
+           {"op": "res_add", "scale": 0.5, "shortcut": {"cin": c, "cout": 2 * c, "k": 1, "stride": 2, "pad": 0}}, _relu(),
+           {"op": "gap"}, _linear(2 * c, 10), {"op": "softmax_ce"}]
+    wl = Workload(name="rp", ops=ops, bounds=[0, len(ops)], K=1, W=1, B=2, in_shape=(3, 8, 8), classes=10,
+                  precision="bf16", lr=0.05, momentum=0.0, steps=1)
+    params = [torch.as_tensor(p, dtype=DT) for p in make_params(wl, 1)[0]]
+    x, y = make_batch(wl, 1, 0, 0)
+    x, y = torch.as_tensor(x, dtype=DT), torch.as_tensor(y, dtype=torch.int64)
+    seen = []
+
+    def rec(t):
+        seen.append(tuple(t.shape))
+        return t
+
+    dlog, saved, loss = N.forward(ops, params, x, y, q=rec)
+    fwd = list(seen)
+    assert fwd == [
+        (2, 3, 8, 8),                       # module input
+        (c, 3, 3, 3), (2, c, 8, 8),         # stem weight; stem output after bias + ReLU (one rounding)
+        (2 * c, c, 3, 3), (2, 2 * c, 4, 4),       # conv1 weight; its output after ReLU
+        (2 * c, 2 * c, 3, 3),                     # conv2 weight; its output is NOT stored on its own
+        (2 * c, c, 1, 1), (2, 2 * c, 4, 4),       # projection weight and its stored output
+        (2, 2 * c, 4, 4),                         # block output after scale + add + ReLU
+        (2, 2 * c, 1, 1),                         # global average pool
+        (10, 2 * c),                              # classifier weight; the logits stay exact
+        (2, 10, 1, 1),                            # d loss / d logits
+    ]
+    seen.clear()
+    dx, grads = N.backward(ops, params, saved, dlog, need_dx=True, q=rec)
+    assert seen == [
+        (10, 2 * c), (2, 2 * c, 1, 1),            # classifier weight; gradient w.r.t. the pooled features
+        (2, 2 * c, 4, 4),                         # pool backward
+        (2, 2 * c, 4, 4),                         # ... after the block output's ReLU mask (idempotent)
+        (2 * c, c, 1, 1),                         # projection weight (its input gradient waits for the sum)
+        (2 * c, 2 * c, 3, 3), (2, 2 * c, 4, 4),   # conv2 weight; gradient w.r.t. conv1's output
+        (2, 2 * c, 4, 4),                         # ... after conv1's ReLU mask
+        (2 * c, c, 3, 3),                         # conv1 weight; its input gradient is not rounded alone
+        (2, c, 8, 8),                             # main + shortcut gradient summed at the block input: one rounding
+        (2, c, 8, 8),                             # ... after the stem's ReLU mask
+        (c, 3, 3, 3), (2, 3, 8, 8),               # stem weight; gradient w.r.t. the images
+    ]
+    # identity rounding = exact mode, bit for bit
+    dlog0, saved0, loss0 = N.forward(ops, params, x, y)
+    dx0, grads0 = N.backward(ops, params, saved0, dlog0, need_dx=True)
+    assert float(loss) == float(loss0) and torch.equal(dx, dx0)
+    assert all(torch.equal(a, b) for a, b in zip(grads, grads0))
+
+
+def test_storage_rounding_mode_stays_within_the_bf16_update_guard_of_the_exact_mode():
+    """bf16 storage moves the gradients of a small residual net by percents -- inside the bf16 update guard of
+    the parity tests (0.15), far above fp32 rounding: the mode is neither a no-op nor a different method."""
+    from oracle import layers as L
+    wl = tiny_resnet(K=1, B=8, c=16)
+    params = _flat_params(wl)
+    x, y = make_batch(wl, 0, 0, 0)
+    x, y = torch.as_tensor(x, dtype=DT), torch.as_tensor(y, dtype=torch.int64)
+    d0, s0, l0 = N.forward(wl.ops, params, x, y)
+    g0 = N.backward(wl.ops, params, s0, d0, need_dx=False)[1]
+    d1, s1, l1 = N.forward(wl.ops, params, x, y, q=L.round_bf16)
+    g1 = N.backward(wl.ops, params, s1, d1, need_dx=False, q=L.round_bf16)[1]
+    rel = [float((a - b).norm() / a.norm()) for a, b in zip(g0, g1)]
+    assert max(rel) < 0.15 and min(rel) > 1e-4, rel
+    assert abs(float(l0) - float(l1)) < 1e-2 * float(l0)
