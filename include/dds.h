@@ -99,7 +99,8 @@ typedef struct dds_spec {
 typedef struct dds_ctx dds_ctx;
 
 /* Integers that drive iteration t (Section 3.2 closed forms). Pure host function, no
- * GPU needed. delays: K per-leg delays d[k0] or NULL for the paper's d[k0] = K-1-k0.
+ * GPU needed; dds_step executes from the very record this call returns (one function inside the
+ * library computes it for both). delays: K per-leg delays d[k0] or NULL for the paper's d[k0] = K-1-k0.
  * out: K records of DDS_SCHED_INTS int32 each:
  *   [0] f = t-k0            mini-batch forwarded (negative: idle)
  *   [1] b = t-k0-2d[k0]     mini-batch back-propagated (negative: idle, no update)
@@ -109,8 +110,14 @@ typedef struct dds_ctx dds_ctx;
  *   [5] error-mailbox slot read  (gradient sent by module k0+1), -1 for the last module
  *   [6] error-mailbox slot written (gradient sent to module k0-1), -1 for module 0
  *   [7] label-queue slot read by the last module's forward, -1 otherwise
+ *   [8] slot of module k0-1's ring holding this module's input for mini-batch f (module k0-1
+ *       forwarded it at iteration f+k0-1; hand-offs are zero-copy), -1 for module 0 or f < 0
+ *   [9] the same for mini-batch b, -1 for module 0 or b < 0
+ *   [10] label-queue slot of mini-batch b (last module: where its loss gradient starts), -1 otherwise
+ *   [11] ring slot that receives the weight snapshot after this iteration's update = (t+1) mod R
+ *   [12] label-queue slot the ingest writes = t mod (K + 2d[K-1]) (module 0), -1 otherwise
  * Returns DDS_EINVAL if delays violate d[K-1] >= 0, d[k0] >= d[k0+1]+1. */
-#define DDS_SCHED_INTS 8
+#define DDS_SCHED_INTS 13
 int dds_schedule(int K, const int* delays, int64_t t, int32_t* out);
 
 /* Bytes of arena dds_create needs for this problem (host computation only). */
@@ -150,9 +157,10 @@ int dds_get_params_replica(dds_ctx* ctx, int module, int replica, float* dst_dev
                            void* hip_stream);
 
 /* Disagreement between the data-groups' weights as the experiment section measures it:
- * delta = max over parameter tensors l (each weight and each bias of every module) and
- * data-groups s of || w_{s,l} - (1/W) sum_r w_{r,l} ||_2, accumulated in fp64 from the fp32
- * master weights. Exactly 0 without a mixing matrix. Synchronises stream. */
+ * delta = max over layers l and data-groups s of || w_{s,l} - (1/W) sum_r w_{r,l} ||_2, where
+ * w_{s,l} is data-group s's weight vector of layer l in the sense of Section 2.1: all parameters
+ * of the layer (weight and bias; gamma and beta of a normalisation) as one vector. Accumulated in
+ * fp64 from the fp32 master weights. Exactly 0 without a mixing matrix. Synchronises stream. */
 int dds_consensus_error(dds_ctx* ctx, double* host_out, void* hip_stream);
 
 /* One iteration t of every module (Algorithm 1 loop body for all S*K agents).
@@ -212,6 +220,25 @@ double dds_gemm_flops_per_step(const dds_ctx* ctx);
  * asynchronous global->LDS kernels (3x3 stride-1 forward / dgrad; 3x3 and stride-2 wgrad). */
 int dds_profile(dds_ctx* ctx, int enable);
 int dds_profile_read(const dds_ctx* ctx, double* out18);
+
+/* Test-only raw view of the delay buffers, so that batch assignment and slot indexing of Section 3.2
+ * (forward of mini-batch t-k0 into slot t mod R; backward of mini-batch t-k0-2d from slot (t-2d) mod R
+ * with the weights of that slot) can be checked bit for bit on the device. Copies one region, as stored,
+ * to dst_device (asynchronous on stream, ordered after the latest dds_step); bytes must equal
+ * dds_debug_bytes(ctx, what, module, index). Regions:
+ *   DDS_DBG_INPUT     module 0, ring slot: the ingested mini-batch, [W*B][H][W][Cpad] in the compute
+ *                     precision (Cpad = in_c rounded up to a 16-byte chunk, pad lanes zero)
+ *   DDS_DBG_OUTPUT    ring slot: the module's output tensor, same layout (logits of the last module: fp32)
+ *   DDS_DBG_ERROR     mailbox slot of the error gradient module+1 sent to this module (layout of its output)
+ *   DDS_DBG_LABELS    label-queue slot: int32 [W*B] (module is ignored but must be valid)
+ *   DDS_DBG_SNAPSHOT  ring slot, index = the module's layer in canonical order: the weight snapshot the
+ *                     backward reads, transposed [cin][k*k][cout rounded up to a 16-byte chunk], compute
+ *                     precision; DDS_EINVAL for a layer nothing back-propagates through
+ * dds_debug_bytes returns the size in bytes or a negative error code. */
+enum { DDS_DBG_INPUT = 0, DDS_DBG_OUTPUT = 1, DDS_DBG_ERROR = 2, DDS_DBG_LABELS = 3, DDS_DBG_SNAPSHOT = 4 };
+int64_t dds_debug_bytes(dds_ctx* ctx, int what, int module, int index);
+int dds_debug_read(dds_ctx* ctx, int what, int module, int index, int slot, void* dst_device, size_t bytes,
+                   void* hip_stream);
 
 const char* dds_last_error(void);
 

@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libdds.so")
 
 DDS_OK, DDS_EINVAL, DDS_ENOMEM, DDS_EHIP, DDS_EUNSUPPORTED = 0, -1, -2, -3, -4
-DDS_SCHED_INTS = 8
+DDS_SCHED_INTS = 13
 OPS = {"conv": 1, "linear": 2, "relu": 3, "maxpool2": 4, "gap": 5, "res_begin": 6, "res_add": 7,
        "softmax_ce": 8, "bn": 9}
 PRECISION = {"f32": 0, "bf16": 1}
@@ -27,7 +27,7 @@ ACTIVATIONS = {"store": 0, "recompute": 1}  # dds_spec.activations
 EXPORTS = ["dds_schedule", "dds_step_size", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
            "dds_get_params", "dds_set_params", "dds_get_params_replica", "dds_consensus_error", "dds_step", "dds_get_loss", "dds_step_count",
            "dds_launches_last_step", "dds_gemm_flops_per_step", "dds_profile", "dds_profile_read",
-           "dds_last_error"]
+           "dds_debug_bytes", "dds_debug_read", "dds_last_error"]
 
 
 class dds_layer(C.Structure):
@@ -81,6 +81,9 @@ def _load():
     lib.dds_gemm_flops_per_step.restype = C.c_double
     lib.dds_profile.argtypes = [vp, C.c_int]
     lib.dds_profile_read.argtypes = [vp, C.POINTER(C.c_double)]
+    lib.dds_debug_bytes.argtypes = [vp, C.c_int, C.c_int, C.c_int]
+    lib.dds_debug_bytes.restype = C.c_int64
+    lib.dds_debug_read.argtypes = [vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, C.c_size_t, vp]
     lib.dds_last_error.restype = C.c_char_p
     return lib
 
@@ -101,6 +104,7 @@ def _delays_arg(delays, K):
 
 
 DDS_ETA_CONSTANT, DDS_ETA_PIECEWISE, DDS_ETA_DIMINISHING = 1, 2, 3
+DDS_DBG_INPUT, DDS_DBG_OUTPUT, DDS_DBG_ERROR, DDS_DBG_LABELS, DDS_DBG_SNAPSHOT = 0, 1, 2, 3, 4
 
 
 def dds_step_size(rule: int, t: int, eta0: float) -> float:
@@ -227,6 +231,16 @@ class Trainer:
 
     def dds_gemm_flops_per_step(self) -> float:
         return float(lib.dds_gemm_flops_per_step(self.ctx))
+
+    def dds_debug_read(self, what: int, module: int, slot: int, index: int = 0) -> np.ndarray:
+        """Raw bytes of one delay-buffer region (see include/dds.h) as a uint8 array."""
+        n = lib.dds_debug_bytes(self.ctx, what, module, index)
+        if n < 0:
+            _check(int(n))
+        dev = self.torch.empty(int(n), dtype=self.torch.uint8, device=self.device)
+        _check(lib.dds_debug_read(self.ctx, what, module, index, slot, dev.data_ptr(), int(n), self._stream()))
+        self.torch.cuda.synchronize(self.device)
+        return dev.cpu().numpy()
 
     def dds_profile(self, enable):
         """0 / False: off; 1 / True: time launches on their concurrent streams; 2: modules serialised."""

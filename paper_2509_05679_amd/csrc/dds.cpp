@@ -213,6 +213,58 @@ int check_delays(int K, const int* delays, std::vector<int>& d) {
   return DDS_OK;
 }
 
+// --------------------------------------------------------------------------- schedule
+// Every integer that drives module k0 at iteration t (Section 3.2 closed forms and the slot arithmetic that
+// follows from them). dds_schedule reports exactly this record and dds_step executes from it: there is no
+// second copy of these formulas in the library.
+struct Sched {
+  int64_t f, b;        // mini-batch forwarded / back-propagated (negative: idle)
+  int R;               // ring depth 2d+1
+  int fwd_slot;        // ring slot the forward writes: t mod R
+  int bwd_slot;        // ring slot (activations and weight snapshot) the backward reads: (t-2d) mod R
+  int err_read;        // error-mailbox slot holding the gradient module k0+1 sent for batch b; -1: last module
+  int err_write;       // slot of module k0-1's mailbox this module's backward writes; -1: module 0
+  int label_fwd;       // label-queue slot of batch f (last module, f >= 0), else -1
+  int in_fwd_slot;     // slot of module k0-1's ring holding its output for batch f (forwarded there at f+k0-1); -1: none
+  int in_bwd_slot;     // the same for batch b
+  int label_bwd;       // label-queue slot of batch b (last module, b >= 0), else -1
+  int snap_write;      // ring slot that receives the weights after this iteration's update: (t+1) mod R
+  int label_write;     // label-queue slot the ingest writes (module 0): t mod depth, else -1
+};
+
+inline int wrap(int64_t x, int n) { return (int)((x % n + n) % n); }
+
+Sched module_schedule(const std::vector<int>& d, int k0, int64_t t) {
+  const int K = (int)d.size();
+  Sched s;
+  s.R = 2 * d[k0] + 1;
+  s.f = t - k0;
+  s.b = t - k0 - 2 * d[k0];
+  s.fwd_slot = wrap(t, s.R);
+  s.bwd_slot = wrap(t - 2 * d[k0], s.R);
+  s.snap_write = wrap(t + 1, s.R);
+  if (k0 < K - 1) {
+    const int lag = 2 * (d[k0] - d[k0 + 1]) - 1;  // iterations between the producer's write and this module's read
+    s.err_read = wrap(t - lag, lag + 1);
+  } else {
+    s.err_read = -1;
+  }
+  if (k0 > 0) {
+    const int lag = 2 * (d[k0 - 1] - d[k0]) - 1;
+    s.err_write = wrap(t, lag + 1);
+    const int Rup = 2 * d[k0 - 1] + 1;
+    s.in_fwd_slot = s.f >= 0 ? wrap(s.f + k0 - 1, Rup) : -1;
+    s.in_bwd_slot = s.b >= 0 ? wrap(s.b + k0 - 1, Rup) : -1;
+  } else {
+    s.err_write = s.in_fwd_slot = s.in_bwd_slot = -1;
+  }
+  const int depth = K + 2 * d[K - 1];
+  s.label_fwd = (k0 == K - 1 && s.f >= 0) ? wrap(s.f, depth) : -1;
+  s.label_bwd = (k0 == K - 1 && s.b >= 0) ? wrap(s.b, depth) : -1;
+  s.label_write = k0 == 0 ? wrap(t, depth) : -1;
+  return s;
+}
+
 // --------------------------------------------------------------------------- planning
 int new_tensor(Module& m, int N, int C, int H, int W, int dt, int kind) {
   Tensor t;
@@ -680,28 +732,14 @@ double count_flops(const dds_ctx& c) {
 }
 
 // --------------------------------------------------------------------------- execution helpers
-struct Exec {
-  dds_ctx& c;
-  Module& m;
-  hipStream_t s;
-  int fslot, bslot;  // ring slots of the forward / backward batch
-  char* tensor_ptr(int ti, int slot) const {
-    const Tensor& t = m.tensors[ti];
-    if (t.kind == T_TEMP) return t.temp;
-    if (t.kind == T_RING) return t.recomputed ? m.area + t.ring_off : m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
-    return nullptr;  // external handled by caller
-  }
-};
-
-char* input_ptr(dds_ctx& c, int k0, int64_t batch) {
-  // module k0 > 0 reads the output of module k0-1 for `batch`, forwarded there at iteration batch + k0 - 1
+// Output of module k0-1 in slot `in_slot` of ITS ring (Sched::in_fwd_slot / in_bwd_slot): module k0's input.
+char* input_ptr(dds_ctx& c, int k0, int in_slot) {
   Module& up = c.mods[k0 - 1];
-  const int slot = (int)((batch + k0 - 1) % up.R);
-  return up.ring + (size_t)slot * up.slot_bytes + up.tensors[up.out_tensor].ring_off;
+  return up.ring + (size_t)in_slot * up.slot_bytes + up.tensors[up.out_tensor].ring_off;
 }
 
-// sign plane of a tensor in the given ring slot (null if it has none)
-char* bits_ptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
+// sign plane of a tensor in the given ring slot (null if it has none); in_slot: see input_ptr
+char* bits_ptr(dds_ctx& c, Module& m, int ti, int slot, int in_slot) {
   const Tensor& t = m.tensors[ti];
   if (t.kind == T_RING) {
     if (!t.has_bits) return nullptr;
@@ -710,28 +748,24 @@ char* bits_ptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
   if (t.kind == T_EXTERNAL) {
     Module& up = c.mods[m.k0 - 1];
     const Tensor& ut = up.tensors[up.out_tensor];
-    const int uslot = (int)((batch + m.k0 - 1) % up.R);
-    return ut.has_bits ? up.ring + (size_t)uslot * up.slot_bytes + ut.bits_off : nullptr;
+    return ut.has_bits ? up.ring + (size_t)in_slot * up.slot_bytes + ut.bits_off : nullptr;
   }
   return nullptr;
 }
 
-char* tptr(dds_ctx& c, Module& m, int ti, int slot, int64_t batch) {
+char* tptr(dds_ctx& c, Module& m, int ti, int slot, int in_slot) {
   const Tensor& t = m.tensors[ti];
   if (t.kind == T_TEMP) return t.temp;
   if (t.kind == T_RING) return t.recomputed ? m.area + t.ring_off : m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
-  return input_ptr(c, m.k0, batch);
+  return input_ptr(c, m.k0, in_slot);
 }
 
-char* gptr(dds_ctx& c, Module& m, int gid, int64_t t) {
+char* gptr(dds_ctx& c, Module& m, int gid, const Sched& sc) {
   if (gid >= 0) return m.grads[gid].ptr;
-  if (gid == G_ERR_IN) {
-    const int lag = m.err_depth - 1;
-    return m.err + (size_t)((t - lag) % m.err_depth) * m.err_bytes;
-  }
+  if (gid == G_ERR_IN) return m.err + (size_t)sc.err_read * m.err_bytes;
   if (gid == G_ERR_OUT) {
     Module& up = c.mods[m.k0 - 1];
-    return up.err + (size_t)(t % up.err_depth) * up.err_bytes;
+    return up.err + (size_t)sc.err_write * up.err_bytes;
   }
   return nullptr;
 }
@@ -782,10 +816,11 @@ BnParams bn_params(dds_ctx& c, Module& m, const Node& nd, int slot, const float*
   return p;
 }
 
-// Forward pass of mini-batch f through the tensors of ring slot `slot`. snap < 0: with the current parameters (the
-// pass of iteration t = f + k0). snap >= 0: the same pass again with the parameter snapshot of that slot, which
-// rebuilds the tensors the recompute policy does not keep (the kernels are deterministic: identical bits).
-void run_forward(dds_ctx& c, Module& m, int slot, int64_t f, hipStream_t s, int snap = -1) {
+// Forward pass of a mini-batch through the tensors of ring slot `slot`; its input (modules above the first) is in
+// slot `in_slot` of the ring of the module below. snap < 0: with the current parameters (the pass of iteration
+// t = f + k0). snap >= 0: the same pass again with the parameter snapshot of that slot, which rebuilds the tensors
+// the recompute policy does not keep (the kernels are deterministic: identical bits).
+void run_forward(dds_ctx& c, Module& m, int slot, int in_slot, hipStream_t s, int snap = -1) {
   const int es = dtype_size(c.dt);
   const size_t snap_off = snap >= 0 ? (size_t)snap * c.copies * m.n_master : 0;
   const float* master = snap >= 0 ? m.snap_master + snap_off : m.master;
@@ -794,8 +829,8 @@ void run_forward(dds_ctx& c, Module& m, int slot, int64_t f, hipStream_t s, int 
     if (nd.kind == N_CE) continue;
     const Tensor& ti = m.tensors[nd.in];
     const Tensor& to = m.tensors[nd.out];
-    char* x = tptr(c, m, nd.in, slot, f);
-    char* y = tptr(c, m, nd.out, slot, f);
+    char* x = tptr(c, m, nd.in, slot, in_slot);
+    char* y = tptr(c, m, nd.out, slot, in_slot);
     switch (nd.kind) {
       case N_CONV: {
         const ParamLayer& L = m.layers[nd.layer];
@@ -804,9 +839,9 @@ void run_forward(dds_ctx& c, Module& m, int slot, int64_t f, hipStream_t s, int 
         p.w = c.dt == DT_BF16 ? (const void*)(work + (size_t)L.off * es) : (const void*)(master + L.off);
         p.y = y;
         p.bias = master + L.off + (long long)L.Cout * L.RS * L.Cinpad;
-        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
+        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, in_slot) : nullptr;
         p.mask = nullptr;
-        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
+        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, in_slot) : nullptr;
         p.zeros = c.zeros;
         p.Nimg = c.N; p.H = ti.H; p.W = ti.W; p.Cx = ti.Cpad;
         p.Ho = to.H; p.Wo = to.W;
@@ -834,8 +869,8 @@ void run_forward(dds_ctx& c, Module& m, int slot, int64_t f, hipStream_t s, int 
         BnParams p = bn_params(c, m, nd, slot, master);
         p.x = x;
         p.y = y;
-        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, f) : nullptr;
-        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, f) : nullptr;
+        p.res = nd.res >= 0 ? tptr(c, m, nd.res, slot, in_slot) : nullptr;
+        p.bits_out = nd.relu ? bits_ptr(c, m, nd.out, slot, in_slot) : nullptr;
         launch_bn_forward(c.dt, p, s);
         ++c.launches;
         break;
@@ -851,16 +886,16 @@ void run_forward(dds_ctx& c, Module& m, int slot, int64_t f, hipStream_t s, int 
   }
 }
 
-void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
-  const int slot = (int)(((t - 2 * m.d) % m.R + m.R) % m.R);
+void run_backward(dds_ctx& c, Module& m, const Sched& sc, hipStream_t s) {
+  const int slot = sc.bwd_slot, in_slot = sc.in_bwd_slot;
   for (int ni = (int)m.nodes.size() - 1; ni >= 0; --ni) {
     const Node& nd = m.nodes[ni];
     if (nd.kind == N_CE) continue;  // dlogits were produced by the loss kernel
     const Tensor& ti = m.tensors[nd.in];
     const Tensor& to = m.tensors[nd.out];
-    char* x = tptr(c, m, nd.in, slot, b);
-    char* gout = gptr(c, m, nd.gout, t);
-    char* gin = gptr(c, m, nd.gin, t);
+    char* x = tptr(c, m, nd.in, slot, in_slot);
+    char* gout = gptr(c, m, nd.gout, sc);
+    char* gin = gptr(c, m, nd.gin, sc);
     switch (nd.kind) {
       case N_CONV: {
         const ParamLayer& L = m.layers[nd.layer];
@@ -894,18 +929,18 @@ void run_backward(dds_ctx& c, Module& m, int64_t t, int64_t b, hipStream_t s) {
           p.w = L.stash + (size_t)slot * L.stash_slot_bytes;
           p.y = gin;
           p.bias = nullptr;
-          p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, t) : nullptr;
+          p.res = nd.addend != G_NONE ? gptr(c, m, nd.addend, sc) : nullptr;
           p.nrep = c.copies;  // data-group r back-propagates through its own snapshot
           p.w_rep = (long long)m.R * L.stash_slot_bytes;
           if (nd.fold_sc >= 0) {
-            const Node& sc = m.nodes[nd.fold_sc];
-            const ParamLayer& Ls = m.layers[sc.layer];
-            p.x2 = gptr(c, m, sc.gout, t);
+            const Node& scn = m.nodes[nd.fold_sc];
+            const ParamLayer& Ls = m.layers[scn.layer];
+            p.x2 = gptr(c, m, scn.gout, sc);
             p.w2 = Ls.stash + (size_t)slot * Ls.stash_slot_bytes;
-            p.Cx2 = m.tensors[sc.out].Cpad;
+            p.Cx2 = m.tensors[scn.out].Cpad;
             p.w2_rep = (long long)m.R * Ls.stash_slot_bytes;
           }
-          p.maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, b) : nullptr;
+          p.maskbits = nd.mask_in ? bits_ptr(c, m, nd.in, slot, in_slot) : nullptr;
           p.mask = nd.mask_in && !p.maskbits ? x : nullptr;
           p.zeros = c.zeros;
           p.Nimg = c.N; p.H = to.H; p.W = to.W; p.Cx = ldg;
@@ -1024,27 +1059,21 @@ int dds_schedule(int K, const int* delays, int64_t t, int32_t* out) {
   int rc = check_delays(K, delays, d);
   if (rc) return rc;
   for (int k0 = 0; k0 < K; ++k0) {
+    const Sched sc = module_schedule(d, k0, t);
     int32_t* o = out + (size_t)k0 * DDS_SCHED_INTS;
-    const int R = 2 * d[k0] + 1;
-    const int64_t f = t - k0, b = t - k0 - 2 * d[k0];
-    o[0] = (int32_t)f;
-    o[1] = (int32_t)b;
-    o[2] = R;
-    o[3] = (int32_t)(t % R);
-    o[4] = (int32_t)(((t - 2 * d[k0]) % R + R) % R);
-    if (k0 < K - 1) {
-      const int lag = 2 * (d[k0] - d[k0 + 1]) - 1;
-      o[5] = (int32_t)(((t - lag) % (lag + 1) + (lag + 1)) % (lag + 1));
-    } else {
-      o[5] = -1;
-    }
-    if (k0 > 0) {
-      const int lag = 2 * (d[k0 - 1] - d[k0]) - 1;
-      o[6] = (int32_t)(t % (lag + 1));
-    } else {
-      o[6] = -1;
-    }
-    o[7] = (k0 == K - 1 && f >= 0) ? (int32_t)(f % (K + 2 * d[K - 1])) : -1;
+    o[0] = (int32_t)sc.f;
+    o[1] = (int32_t)sc.b;
+    o[2] = sc.R;
+    o[3] = sc.fwd_slot;
+    o[4] = sc.bwd_slot;
+    o[5] = sc.err_read;
+    o[6] = sc.err_write;
+    o[7] = sc.label_fwd;
+    o[8] = sc.in_fwd_slot;
+    o[9] = sc.in_bwd_slot;
+    o[10] = sc.label_bwd;
+    o[11] = sc.snap_write;
+    o[12] = sc.label_write;
   }
   return DDS_OK;
 }
@@ -1209,10 +1238,13 @@ int dds_consensus_error(dds_ctx* c, double* host_out, void* stream) {
     host.resize(n);
     HIP_TRY(hipMemcpyAsync(host.data(), m.cons_dev, n * sizeof(double), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    sums.assign((size_t)2 * m.layers.size() * c->W, 0.0);  // [layer][part][s], blocks added in order
+    // a layer's weight vector w_l (Section 2.1) is its weight and its bias together: [layer][s], both parts
+    // of every block added in order
+    sums.assign(m.layers.size() * c->W, 0.0);
     for (int b = 0; b < m.blocks_update; ++b) {
       const int layer = m.map_update_host[2 * b];
-      for (int e = 0; e < 2 * c->W; ++e) sums[(size_t)layer * 2 * c->W + e] += host[(size_t)b * 2 * c->W + e];
+      for (int part = 0; part < 2; ++part)
+        for (int r = 0; r < c->W; ++r) sums[(size_t)layer * c->W + r] += host[((size_t)2 * b + part) * c->W + r];
     }
     for (double v : sums) worst = v > worst ? v : worst;
   }
@@ -1240,10 +1272,11 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
   // ingest: caller batches -> module 0's ring slot t mod R_0 (layout + precision), labels -> queue
   {
     Module& m0 = c->mods[0];
+    const Sched sc0 = module_schedule(c->d, 0, t);
     IngestParams p{};
     for (int s = 0; s < c->W; ++s) { p.x[s] = x[s]; p.y[s] = y[s]; }
-    p.dst = m0.ring + (size_t)(t % m0.R) * m0.slot_bytes + m0.tensors[0].ring_off;
-    p.labels = c->labels + (size_t)(t % c->label_depth) * c->N;
+    p.dst = m0.ring + (size_t)sc0.fwd_slot * m0.slot_bytes + m0.tensors[0].ring_off;
+    p.labels = c->labels + (size_t)sc0.label_write * c->N;
     p.W = c->W; p.B = c->B; p.C = c->in_c; p.HW = c->in_h * c->in_w; p.Cpad = m0.tensors[0].Cpad;
     launch_ingest(c->dt, p, us);
     ++c->launches;
@@ -1267,37 +1300,30 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
         HIP_TRY(hipStreamWaitEvent(s, c->fork, 0));
       }
     }
-    const int64_t f = t - k0, b = t - k0 - 2 * m.d;
+    const Sched sc = module_schedule(c->d, k0, t);
     const bool last = k0 == c->K - 1;
-    const int bslot = (int)(((t - 2 * m.d) % m.R + m.R) % m.R);
-    if (f >= 0) run_forward(*c, m, (int)(t % m.R), f, s);
-    if (last && f >= 0) {
+    if (sc.f >= 0) run_forward(*c, m, sc.fwd_slot, sc.in_fwd_slot, s);
+    if (last && sc.f >= 0) {
       const Node& ce = m.nodes.back();
       const Tensor& lt = m.tensors[ce.in];
-      const int ldg = lt.Cpad;
-      {
-        const float* logits = (const float*)tptr(*c, m, ce.in, (int)(t % m.R), f);
-        const int32_t* lab = c->labels + (size_t)(f % c->label_depth) * c->N;
-        void* dl = (b == f) ? gptr(*c, m, ce.gin, t) : nullptr;
-        launch_softmax_ce(c->dt, logits, lab, dl, c->loss, c->W, c->B, c->classes, lt.Cpad, ldg, s);
-        ++c->launches;
-        c->have_loss = true;
-      }
+      const float* logits = (const float*)tptr(*c, m, ce.in, sc.fwd_slot, sc.in_fwd_slot);
+      const int32_t* lab = c->labels + (size_t)sc.label_fwd * c->N;
+      void* dl = (sc.b == sc.f) ? gptr(*c, m, ce.gin, sc) : nullptr;
+      launch_softmax_ce(c->dt, logits, lab, dl, c->loss, c->W, c->B, c->classes, lt.Cpad, lt.Cpad, s);
+      ++c->launches;
+      c->have_loss = true;
     }
-    if (m.recompute && b >= 0) run_forward(*c, m, bslot, b, s, bslot);
-    if (last) {
+    if (m.recompute && sc.b >= 0) run_forward(*c, m, sc.bwd_slot, sc.in_bwd_slot, s, sc.bwd_slot);
+    if (last && sc.b >= 0 && sc.b != sc.f) {  // a delayed last module: the loss gradient of the batch forwarded 2d iterations ago
       const Node& ce = m.nodes.back();
       const Tensor& lt = m.tensors[ce.in];
-      const int ldg = lt.Cpad;
-      if (b >= 0 && b != f) {
-        const float* logits = (const float*)tptr(*c, m, ce.in, bslot, b);
-        const int32_t* lab = c->labels + (size_t)(b % c->label_depth) * c->N;
-        launch_softmax_ce(c->dt, logits, lab, gptr(*c, m, ce.gin, t), nullptr, c->W, c->B, c->classes, lt.Cpad, ldg, s);
-        ++c->launches;
-      }
+      const float* logits = (const float*)tptr(*c, m, ce.in, sc.bwd_slot, sc.in_bwd_slot);
+      const int32_t* lab = c->labels + (size_t)sc.label_bwd * c->N;
+      launch_softmax_ce(c->dt, logits, lab, gptr(*c, m, ce.gin, sc), nullptr, c->W, c->B, c->classes, lt.Cpad, lt.Cpad, s);
+      ++c->launches;
     }
-    if (b >= 0) {
-      run_backward(*c, m, t, b, s);
+    if (sc.b >= 0) {
+      run_backward(*c, m, sc, s);
       if (!c->gossip) {
         launch_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->W, step, c->mu, s);
       } else {
@@ -1305,9 +1331,9 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
         launch_gossip_update(c->dt, m.descs_dev, m.map_update_dev, m.blocks_update, c->P_dev, c->W, m.n_master, step,
                              c->mu, s);
       }
-      launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, (int)((t + 1) % m.R), s);
+      launch_stash(c->dt, m.descs_dev, m.map_stash_dev, m.blocks_stash * c->copies, sc.snap_write, s);
       c->launches += 2;
-      if (m.recompute) HIP_TRY(snapshot_params(*c, m, (int)((t + 1) % m.R), s));
+      if (m.recompute) HIP_TRY(snapshot_params(*c, m, sc.snap_write, s));
     }
     if (multi) HIP_TRY(hipEventRecord(m.done[t & 1], s));
   }
@@ -1334,6 +1360,72 @@ int dds_step(dds_ctx* c, const float* const* x, const int32_t* const* y, float l
     }
     c->prof_pending.clear();
   }
+  return DDS_OK;
+}
+
+// Test-only raw view of the delay buffers.
+static int debug_region(dds_ctx* c, int what, int module, int index, int slot, char** ptr, size_t* bytes) {
+  if (!c || module < 0 || module >= c->K) return fail(DDS_EINVAL, "dds_debug: bad ctx / module");
+  Module& m = c->mods[module];
+  switch (what) {
+    case DDS_DBG_INPUT: {
+      if (module != 0) return fail(DDS_EINVAL, "dds_debug: only module 0 keeps its input in its own ring");
+      if (slot < 0 || slot >= m.R) return fail(DDS_EINVAL, "dds_debug: ring slot %d out of [0,%d)", slot, m.R);
+      const Tensor& t = m.tensors[0];
+      *ptr = m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
+      *bytes = t.bytes;
+      return DDS_OK;
+    }
+    case DDS_DBG_OUTPUT: {
+      if (slot < 0 || slot >= m.R) return fail(DDS_EINVAL, "dds_debug: ring slot %d out of [0,%d)", slot, m.R);
+      const Tensor& t = m.tensors[m.out_tensor];
+      *ptr = m.ring + (size_t)slot * m.slot_bytes + t.ring_off;
+      *bytes = t.bytes;
+      return DDS_OK;
+    }
+    case DDS_DBG_ERROR: {
+      if (module >= c->K - 1) return fail(DDS_EINVAL, "dds_debug: the last module has no error mailbox");
+      if (slot < 0 || slot >= m.err_depth) return fail(DDS_EINVAL, "dds_debug: mailbox slot %d out of [0,%d)", slot, m.err_depth);
+      *ptr = m.err + (size_t)slot * m.err_bytes;
+      *bytes = m.tensors[m.out_tensor].bytes;
+      return DDS_OK;
+    }
+    case DDS_DBG_LABELS: {
+      if (slot < 0 || slot >= c->label_depth) return fail(DDS_EINVAL, "dds_debug: label slot %d out of [0,%d)", slot, c->label_depth);
+      *ptr = (char*)(c->labels + (size_t)slot * c->N);
+      *bytes = sizeof(int32_t) * c->N;
+      return DDS_OK;
+    }
+    case DDS_DBG_SNAPSHOT: {
+      if (index < 0 || index >= (int)m.layers.size()) return fail(DDS_EINVAL, "dds_debug: layer %d out of range", index);
+      const ParamLayer& L = m.layers[index];
+      if (!L.need_stash) return fail(DDS_EINVAL, "dds_debug: layer %d keeps no snapshots (nothing back-propagates through it)", index);
+      if (slot < 0 || slot >= m.R) return fail(DDS_EINVAL, "dds_debug: ring slot %d out of [0,%d)", slot, m.R);
+      *ptr = L.stash + (size_t)slot * L.stash_slot_bytes;
+      *bytes = (size_t)L.stash_elems * dtype_size(c->dt);
+      return DDS_OK;
+    }
+    default:
+      return fail(DDS_EINVAL, "dds_debug: unknown region %d", what);
+  }
+}
+
+int64_t dds_debug_bytes(dds_ctx* c, int what, int module, int index) {
+  char* p = nullptr;
+  size_t n = 0;
+  const int rc = debug_region(c, what, module, index, 0, &p, &n);
+  return rc ? (int64_t)rc : (int64_t)n;
+}
+
+int dds_debug_read(dds_ctx* c, int what, int module, int index, int slot, void* dst, size_t bytes, void* stream) {
+  char* p = nullptr;
+  size_t n = 0;
+  if (int rc = debug_region(c, what, module, index, slot, &p, &n)) return rc;
+  if (!dst || bytes != n) return fail(DDS_EINVAL, "dds_debug_read: the region has %zu bytes, caller passed %zu", n, bytes);
+  hipStream_t s = (hipStream_t)stream;
+  c->chained = false;
+  if (int rc = order_after_last_step(c, s)) return rc;
+  HIP_TRY(hipMemcpyAsync(dst, p, n, hipMemcpyDeviceToDevice, s));
   return DDS_OK;
 }
 

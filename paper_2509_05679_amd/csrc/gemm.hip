@@ -562,12 +562,12 @@ struct HaloGeom {
 // (KB/16); patch rows use bits of the patch coordinates (see patch_swizzle), and the pixels
 // of a 32-pixel fragment are dealt to lanes so that one cycle's lanes hold 16 consecutive ones.
 __device__ __forceinline__ void dma16(const void* gsrc, uint32_t lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base_uniform) : "memory");
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gsrc), "s"(lds_base_uniform) : "memory", "m0");
 }
 // Same copy with the address split into a wave-uniform 64-bit base (SGPR pair) and a per-lane
 // unsigned 32-bit byte offset: the per-copy address arithmetic stays on the scalar unit.
 __device__ __forceinline__ void dma16s(const void* gbase_uniform, uint32_t goff, uint32_t lds_base_uniform) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(goff), "s"(gbase_uniform), "s"(lds_base_uniform) : "memory");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(goff), "s"(gbase_uniform), "s"(lds_base_uniform) : "memory", "m0");
 }
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 __device__ __forceinline__ void wg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
@@ -875,11 +875,7 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) =
       const int n = n0 + gc * (16 / ES);
       const size_t pix = ((size_t)gi * p.H + h0 + y) * p.W + w0 + x;
       const u32x4_t v = *(const u32x4_t DDS_LDS_AS*)((const char DDS_LDS_AS*)smem + out_off + f * 1024 + lane * 16);
-#ifdef DDS_NT_STORE
-      if (gi < p.Nimg && n < p.ldy) __builtin_nontemporal_store(v, (u32x4_t*)((char*)p.y + (pix * p.ldy + n) * ES));
-#else
       if (gi < p.Nimg && n < p.ldy) *(u32x4_t*)((char*)p.y + (pix * p.ldy + n) * ES) = v;
-#endif
     }
   }
 }
