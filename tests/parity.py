@@ -1,10 +1,52 @@
-"""Shared helpers of the GPU parity tests: run the HIP library and the CPU oracle on
-the same seeded workload and compare parameter trajectories tensor by tensor."""
+"""Shared helpers of the parity tests: run the HIP library and the CPU oracle on the same
+seeded workload and compare parameter trajectories tensor by tensor.
+
+What is asserted (check_parity), per compared step:
+  * the stated bar: relative L2 error of every layer weight vector w_l = (weight, bias)
+    against the exact fp64 oracle (1e-4 fp32 / 2e-2 bf16);
+  * per parameter tensor, the L2 error relative to the accumulated UPDATE p(T) - p(0) of the
+    oracle (the "update guard"): an update is ~1e-2 of a weight norm, so this is the assertion
+    that carries the load. Measured on the ResNet-18 shapes at per-group batch 4 over 16
+    iterations, a run that never updates scores at worst 2.9e-2 on the stated bar (most layers
+    would pass it) and a run that back-propagates through the current instead of the
+    forward-time weights scores 2.6e-3 on it, but 1.0 and 0.23 on the update guard;
+  * per parameter tensor, the element-wise figure max|hip - oracle| / rms(oracle update): a
+    norm cannot see one wrong element in 10^4, this can;
+  * on the bf16 path additionally the update guard and the element-wise figure against the
+    oracle's storage-rounding mode (oracle.network, q = round-to-nearest-even bf16), which
+    rounds where the library stores bf16 and is otherwise the same fp64 recurrence: what is
+    left between the two is accumulation order, so the bound is tight (5e-2) where the bound
+    against the exact oracle has to leave room for bf16 rounding itself (0.15).
+tests/test_parity_sensitivity.py feeds deliberately wrong CPU variants through check_parity and
+requires every threshold set used by the GPU tests to reject them.
+"""
 from __future__ import annotations
 
 import numpy as np
 
 from dds_inputs import make_batch, make_params, param_shapes
+
+# Stated bar: relative L2 error of every layer weight vector w_l = (weight, bias).
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+# Update guard against the exact oracle. The fp32 figure leaves room for the handful of ReLU /
+# max-pool decisions that fp32 and fp64 arithmetic take differently (each moves one element of a
+# mean gradient); the bf16 figure for bf16 rounding of activations, weights and error gradients.
+UPDATE_TOL = {"f32": 2e-2, "bf16": 1.5e-1}
+# toy networks have too few near-zero pre-activations for a decision to flip
+UPDATE_TOL_TINY_F32 = 1e-3
+# Update guard of the bf16 path against the oracle's storage-rounding mode.
+UPDATE_TOL_ROUNDED = 5e-2
+# Element-wise figure, fp32 path against the exact oracle: toy networks / benchmark shapes.
+ELEM_TOL_F32_TINY = 1e-2
+ELEM_TOL_F32 = 1e-1
+# Element-wise figure, bf16 path against the storage-rounding mode (a single element whose
+# value is plainly wrong sits at 1 or above).
+ELEM_TOL_ROUNDED = 0.5
+
+
+def bf16_round():
+    from oracle import layers
+    return layers.round_bf16
 
 
 def run_hip(wl, seed, T, delays=None, every_step=False, lr_schedule=None, activations="store"):
@@ -37,10 +79,10 @@ def run_hip(wl, seed, T, delays=None, every_step=False, lr_schedule=None, activa
     return traj, losses
 
 
-def run_oracle(wl, seed, T, delays=None, every_step=False, lr_schedule=None):
-    import torch
+def run_oracle(wl, seed, T, delays=None, every_step=False, lr_schedule=None, q=None, pipeline_cls=None):
     from oracle import fdg
-    pipe = fdg.Pipeline(wl.ops, wl.bounds, wl.W, make_params(wl, seed), wl.lr, wl.momentum, delays)
+    cls = fdg.Pipeline if pipeline_cls is None else pipeline_cls
+    pipe = cls(wl.ops, wl.bounds, wl.W, make_params(wl, seed), wl.lr, wl.momentum, delays, q=q)
     pipe.keep_history = False
     traj, losses = [], []
     for t in range(T):
@@ -64,14 +106,15 @@ def tensor_slices(wl, k0):
 
 
 def rel_errors(wl, hip_params, orc_params, init=None):
-    """Relative L2 errors ||hip - oracle|| / ||oracle||.
+    """Errors of hip_params against orc_params (lists over modules of flat arrays).
 
-    Returns (layer_rows, tensor_rows). A layer row groups a layer's weight and bias into
-    the paper's layer weight vector w_l (Section 2.1: "the vectorization of the weight in
-    the layer l"): (module, layer name, rel). A tensor row is per parameter tensor:
-    (module, tensor name, rel on the parameter, rel on the update p(T) - p(0));
-    the parameter ratio of a tensor the oracle leaves at exactly zero is 0 if the HIP side
-    is exactly zero too and inf otherwise."""
+    Returns (layer_rows, tensor_rows). A layer row groups a layer's weight and bias into one
+    layer weight vector w_l, the unit in which Section 2.1 indexes the weights:
+    (module, layer name, relative L2 error). A tensor row is per parameter tensor:
+    (module, tensor name, relative L2 error on the parameter, L2 error relative to the update
+    p(T) - p(0), element-wise figure max|hip - oracle| / rms(p(T) - p(0))).
+    The parameter ratio of a tensor the oracle leaves at exactly zero is 0 if the HIP side
+    is exactly zero too and inf otherwise; the two update figures are None without `init`."""
     layer_rows, tensor_rows = [], []
     for k0 in range(wl.K):
         groups = {}
@@ -80,15 +123,18 @@ def rel_errors(wl, hip_params, orc_params, init=None):
             nb = np.linalg.norm(b)
             err = np.linalg.norm(a - b)
             rel = err / nb if nb > 0 else (0.0 if err == 0 else np.inf)
-            upd = None
+            upd = elem = None
             if init is not None:
                 i0 = init[k0][sl]
                 du = np.linalg.norm(b - i0)
+                emax = float(np.max(np.abs(a - b))) if a.size else 0.0
                 # "no update yet": the oracle's fp64 mixing sum_r (1/S) w can move a weight by an ulp
                 # of fp64 when 1/S is not a power of two, which is not an update to compare against
                 floor = 1e-13 * max(np.linalg.norm(i0), 1.0)
                 upd = (err / du) if du > floor else (0.0 if err <= floor else np.inf)
-            tensor_rows.append((k0, name, rel, upd))
+                rms = du / np.sqrt(max(a.size, 1))
+                elem = (emax / rms) if du > floor else (0.0 if emax <= floor else np.inf)
+            tensor_rows.append((k0, name, rel, upd, elem))
             g = groups.setdefault(name.rsplit(".", 1)[0], [0.0, 0.0])
             g[0] += err ** 2
             g[1] += nb ** 2
@@ -99,3 +145,50 @@ def rel_errors(wl, hip_params, orc_params, init=None):
 
 def flat_init(wl, seed):
     return [np.concatenate([p.ravel().astype(np.float64) for p in m]) for m in make_params(wl, seed)]
+
+
+def check_parity(wl, got, want, init, tol=None, update_tol=None, elem_tol=None, label="", verbose=True,
+                 skip=()):
+    """Asserts every compared step of trajectory `got` against `want` (lists over steps of lists over
+    modules of flat arrays). tol: bound on every layer row (None: not asserted); update_tol: bound on
+    every tensor's update-relative error; elem_tol: bound on every tensor's element-wise figure (None:
+    reported only). skip: tensor names exempt from the update figures (parameters whose gradient is
+    identically zero). Returns (worst layer rel, worst update-rel, worst element-wise figure)."""
+    worst = worst_u = worst_e = 0.0
+    for step, (hp, op) in enumerate(zip(got, want)):
+        layer_rows, tensor_rows = rel_errors(wl, hp, op, init)
+        if verbose and step == len(got) - 1:
+            for k0, name, rel in sorted(layer_rows, key=lambda r: -r[2])[:3]:
+                print(f"[parity{label}]   layer  module {k0} {name}: rel {rel:.3e}", flush=True)
+            for k0, name, rel, upd, elem in sorted(tensor_rows, key=lambda r: -r[3])[:3]:
+                print(f"[parity{label}]   tensor module {k0} {name}: rel {rel:.3e} update-rel {upd:.3e} "
+                      f"max-elem/rms-update {elem:.3e}", flush=True)
+        for k0, name, rel in layer_rows:
+            worst = max(worst, rel)
+            if tol is not None:
+                assert rel <= tol, f"{label} step-index {step} module {k0} layer {name}: rel {rel:.3e} > {tol}"
+        for k0, name, rel, upd, elem in tensor_rows:
+            if name in skip:
+                continue
+            worst_u = max(worst_u, upd)
+            worst_e = max(worst_e, elem)
+            if update_tol is not None:
+                assert upd <= update_tol, f"{label} step-index {step} module {k0} {name}: update-rel {upd:.3e} > {update_tol}"
+            if elem_tol is not None:
+                assert elem <= elem_tol, (f"{label} step-index {step} module {k0} {name}: max element error / rms update "
+                                          f"{elem:.3e} > {elem_tol}")
+    if verbose:
+        print(f"[parity{label}] worst layer rel {worst:.3e}, worst tensor update-rel {worst_u:.3e}, "
+              f"worst max-elem/rms-update {worst_e:.3e}", flush=True)
+    return worst, worst_u, worst_e
+
+
+def thresholds(precision, tiny=False):
+    """The threshold sets the GPU tests use: a list of (oracle mode, kwargs of check_parity).
+    fp32: against the exact oracle. bf16: the stated bar and the loose update guard against the exact
+    oracle, the tight update guard and the element-wise bound against the storage-rounding mode."""
+    if precision == "f32":
+        return [("exact", dict(tol=TOL["f32"], update_tol=UPDATE_TOL_TINY_F32 if tiny else UPDATE_TOL["f32"],
+                               elem_tol=ELEM_TOL_F32_TINY if tiny else ELEM_TOL_F32))]
+    return [("exact", dict(tol=TOL["bf16"], update_tol=UPDATE_TOL["bf16"], elem_tol=None)),
+            ("rounded", dict(tol=TOL["bf16"], update_tol=UPDATE_TOL_ROUNDED, elem_tol=ELEM_TOL_ROUNDED))]

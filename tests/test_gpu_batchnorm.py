@@ -5,23 +5,21 @@ import pytest
 
 from dds_inputs import workload
 from dds_inputs.configs import ring_mixing, tiny_cnn, tiny_resnet
-from parity import flat_init, rel_errors, run_hip, run_oracle, tensor_slices
+from parity import bf16_round, check_parity, flat_init, rel_errors, run_hip, run_oracle, tensor_slices, thresholds
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-4, "bf16": 2e-2}
-# Guard rail on single tensors, measured against the accumulated update (see test_gpu_parity.py):
-# applied in fp32, where it holds every tensor of every normalised net below (also at the full
-# channel counts and image sizes) to <= 2e-2, i.e. the algebra is right. In bf16 it is reported but
-# not asserted: the library stores the convolution output in bf16 before normalising it, and for the
-# elements whose normalised value lies within that quantisation step of zero the ReLU decision differs
-# from the fp64 oracle's (0.1-0.3 % of the elements). Each such flip changes the back-propagated
-# gradient by its full value at that element, so the gradients upstream of a normalised ReLU move by
-# about sqrt(fraction) = 3-6 % per such layer (0.1-0.4 observed on single tensors after several), while
-# gamma / beta of the layer itself move by tenths of a percent. tests/test_oracle_network.py reproduces
-# the effect inside the oracle by quantising that one tensor. The stated bar, relative error of every
-# layer weight vector <= 2e-2, is asserted in both precisions.
-UPDATE_TOL = {"f32": 2e-2, "bf16": float("inf")}
+# Against the exact fp64 oracle the bf16 path of a normalised net cannot be held to a tight per-tensor bound:
+# the library stores the convolution output in bf16 before normalising it, and for the elements whose
+# normalised value lies within that quantisation step of zero the ReLU decision differs from the exact
+# oracle's (0.1-0.3 % of the elements). Each such flip changes the back-propagated gradient by its full
+# value at that element, so the gradients upstream of a normalised ReLU move by about sqrt(fraction) = 3-6 %
+# per such layer (0.1-0.4 observed on single tensors after several), while gamma / beta of the layer itself
+# move by tenths of a percent (tests/test_oracle_network.py reproduces the effect inside the oracle). The
+# oracle's storage-rounding mode takes those decisions on the same bf16 values as the library, so against it
+# the tight update guard and the element-wise bound of tests/parity.py apply; against the exact oracle the
+# stated bar (layer weight vectors <= 2e-2) is asserted and single tensors are held to 0.5.
+EXACT_UPDATE_TOL_BF16_BN = 0.5
 # A convolution bias that feeds a normalisation has an exactly zero gradient in exact arithmetic
 # (the normalisation removes any per-channel constant): the oracle leaves it at ~1e-17, fp32 /
 # bf16 arithmetic at rounding-noise level, so a ratio of the two says nothing. Those tensors are
@@ -35,54 +33,46 @@ def _dead_biases(wl, k0):
             if op["op"] == "conv" and i + 1 < len(ops) and ops[i + 1]["op"] == "bn"}
 
 
-def _compare(wl, seed, T, every_step=True, update_tol=None):
-    tol = TOL[wl.precision]
-    update_tol = UPDATE_TOL[wl.precision] if update_tol is None else update_tol
+def _compare(wl, seed, T, every_step=True, tiny=False):
     print(f"[bn] {wl.name} K={wl.K} W={wl.W} B={wl.B} {wl.precision} T={T} seed={seed}", flush=True)
     hip, hl = run_hip(wl, seed, T, None, every_step)
-    orc, ol = run_oracle(wl, seed, T, None, every_step)
     init = flat_init(wl, seed)
-    dead = [_dead_biases(wl, k0) for k0 in range(wl.K)]
-    worst = worst_u = 0.0
-    for step, (hp, op) in enumerate(zip(hip, orc)):
-        layer_rows, tensor_rows = rel_errors(wl, hp, op, init)
-        for k0, name, rel in layer_rows:
-            worst = max(worst, rel)
-            assert rel <= tol, f"step-index {step} module {k0} layer {name}: rel {rel:.3e} > {tol}"
-        for k0, name, rel, upd in tensor_rows:
-            if name in dead[k0]:
-                sl = dict(tensor_slices(wl, k0))[name]
-                err = float(np.abs(hp[k0][sl] - op[k0][sl]).max())
-                assert err <= DEAD_BIAS_ABS[wl.precision], f"step-index {step} module {k0} {name}: abs {err:.3e}"
-                continue
-            worst_u = max(worst_u, upd)
-            assert upd <= update_tol, f"step-index {step} module {k0} {name}: update-rel {upd:.3e} > {update_tol}"
-    for t, (a, b) in enumerate(zip(hl, ol)):
-        assert (a is None) == (b is None)
-        if a is not None:
-            assert abs(a - b) <= max(10 * tol * abs(b), 1e-5), f"loss at t={t}: {a} vs {b}"
-    for k0, name, rel, upd in sorted((r for r in tensor_rows if r[1] not in dead[r[0]]), key=lambda r: -r[3])[:3]:
-        print(f"[bn]   tensor module {k0} {name}: rel {rel:.3e} update-rel {upd:.3e}", flush=True)
-    print(f"[bn] worst layer rel {worst:.3e}, worst tensor update-rel {worst_u:.3e}", flush=True)
+    dead = set().union(*[_dead_biases(wl, k0) for k0 in range(wl.K)])
+    for mode, kw in thresholds(wl.precision, tiny):
+        if wl.precision == "bf16" and mode == "exact":
+            kw = dict(kw, update_tol=EXACT_UPDATE_TOL_BF16_BN)
+        orc, ol = run_oracle(wl, seed, T, None, every_step, q=bf16_round() if mode == "rounded" else None)
+        check_parity(wl, hip, orc, init, label=" bn " + mode, skip=dead, **kw)
+        for hp, op in zip(hip, orc):
+            for k0 in range(wl.K):
+                for name, sl in tensor_slices(wl, k0):
+                    if name in _dead_biases(wl, k0):
+                        err = float(np.abs(hp[k0][sl] - op[k0][sl]).max())
+                        assert err <= DEAD_BIAS_ABS[wl.precision], f"module {k0} {name}: abs {err:.3e}"
+        loss_tol = 10 * kw["tol"] if mode == "exact" else 5e-3
+        for t, (a, b) in enumerate(zip(hl, ol)):
+            assert (a is None) == (b is None)
+            if a is not None:
+                assert abs(a - b) <= max(loss_tol * abs(b), 1e-5), f"loss at t={t} ({mode} oracle): {a} vs {b}"
 
 
 def test_tiny_resnet_bn_every_step_fp32():
-    _compare(tiny_resnet(K=3, W=2, B=4, bn=True), seed=21, T=10, update_tol=1e-3)
+    _compare(tiny_resnet(K=3, W=2, B=4, bn=True), seed=21, T=10, tiny=True)
 
 
 def test_tiny_resnet_bn_single_module_single_group_fp32():
-    _compare(tiny_resnet(K=1, W=1, B=6, bn=True), seed=22, T=5, update_tol=1e-3)
+    _compare(tiny_resnet(K=1, W=1, B=6, bn=True), seed=22, T=5, tiny=True)
 
 
 def test_channel_counts_off_the_eight_channel_grid_fp32():
     # 4 and 12 channels: fp32 rows whose last group of eight is half empty
-    _compare(tiny_resnet(K=2, W=2, B=3, c=4, bn=True), seed=23, T=6, update_tol=1e-3)
-    _compare(tiny_resnet(K=2, W=3, B=5, c=6, hw=6, bn=True), seed=24, T=6, update_tol=1e-3)
+    _compare(tiny_resnet(K=2, W=2, B=3, c=4, bn=True), seed=23, T=6, tiny=True)
+    _compare(tiny_resnet(K=2, W=3, B=5, c=6, hw=6, bn=True), seed=24, T=6, tiny=True)
 
 
 def test_normalisation_in_front_of_max_pooling_with_momentum_fp32():
     # conv - bn - relu - maxpool: the pooling backward masks by the normalised ReLU output; momentum 0.9
-    _compare(tiny_cnn(K=2, W=2, B=4, bn=True), seed=30, T=8, update_tol=1e-3)
+    _compare(tiny_cnn(K=2, W=2, B=4, bn=True), seed=30, T=8, tiny=True)
 
 
 def test_tiny_resnet_bn_bf16():

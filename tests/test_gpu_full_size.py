@@ -1,15 +1,23 @@
-"""Full-size checks (the shapes bench.py times: 4 x 128 images, ResNet-18 widths) of the paths beyond
-the exact-mean hot path, on what the oracle can compute one piece at a time: the loss of mini-batch 0
-at the initial weights and the last module's first update (iteration K-1), which need one full-batch
-forward and the last module's backward only."""
+"""Full-size checks (the shapes and the launch configuration bench.py times: 4 x 128 images) on what the
+oracle can compute one piece at a time. Mini-batch 0 is forwarded by module k0 at iteration k0 <= K-1 and the
+first update anywhere happens at the end of iteration K-1, so it travels through every module at the initial
+weights; its backward pass uses the weights of its forward pass (Section 3.2). Module k0's first update, at
+iteration 2(K-1)-k0, is therefore one locked backpropagation of mini-batch 0 at w(0) (the definition form of
+Section 3.3 with a constant weight history): one oracle forward + backward of the whole network per
+data-group covers the first update of ALL K modules, i.e. every forward, dgrad and wgrad launch of the
+benchmark configuration."""
 import numpy as np
 import pytest
 
 from dds_inputs import make_batch, make_params, workload
 from dds_inputs.configs import ring_mixing
-from parity import tensor_slices
+from parity import (ELEM_TOL_F32, ELEM_TOL_ROUNDED, UPDATE_TOL, UPDATE_TOL_ROUNDED, bf16_round, check_parity,
+                    flat_init, tensor_slices)
 
 pytestmark = pytest.mark.gpu
+
+# oracle results by (workload, precision, seed, mode): the mixing test reuses the exact-mean test's gradients
+_ORACLE = {}
 
 
 def _dead_biases(wl, k0):
@@ -19,81 +27,110 @@ def _dead_biases(wl, k0):
             if op["op"] == "conv" and i + 1 < len(ops) and ops[i + 1]["op"] == "bn"}
 
 
-def _first_update(wl, seed, mixing, update_tol, rel_tol):
+def _first_updates(wl, seed, mixing=None, exact_update_tol=None):
+    """Every module's parameters right after its first update, for every data-group, against the oracle's
+    locked backpropagation of mini-batch 0 at the initial weights."""
     import torch
-    from oracle import network as N
+    from oracle import fdg
     import paper_2509_05679_amd as P
-    K = wl.K
-    tr = P.Trainer(P.Spec.from_workload(wl, mixing), wl.W)
+    K, W = wl.K, wl.W
+    print(f"[full] {wl.name} K={K} W={W} B={wl.B} {wl.precision} seed={seed} mixing={'P' if mixing is not None else 'mean'}",
+          flush=True)
+    tr = P.Trainer(P.Spec.from_workload(wl, mixing), W)
     init = make_params(wl, seed)
     for k0 in range(K):
         tr.dds_set_params(k0, init[k0])
-    for t in range(K):
-        xs = [torch.from_numpy(make_batch(wl, seed, t, s)[0]).cuda() for s in range(wl.W)]
-        ys = [torch.from_numpy(make_batch(wl, seed, t, s)[1]).cuda() for s in range(wl.W)]
+    hip = [None] * K       # hip[k0][s]: flat parameters of data-group s
+    loss_hip = delta_hip = first_hip = None
+    for t in range(2 * (K - 1) + 1):
+        xs = [torch.from_numpy(make_batch(wl, seed, t, s)[0]).cuda() for s in range(W)]
+        ys = [torch.from_numpy(make_batch(wl, seed, t, s)[1]).cuda() for s in range(W)]
         tr.dds_step(xs, ys)
-    torch.cuda.synchronize()
-    loss_hip = tr.dds_get_loss()
-    last_hip = [tr.dds_get_params_replica(K - 1, s) for s in range(wl.W)]
-    first_hip = tr.dds_get_params(0)
-    delta_hip = tr.dds_consensus_error()
+        if t == K - 1:
+            loss_hip = tr.dds_get_loss()          # mini-batch 0 at the initial weights
+            delta_hip = tr.dds_consensus_error()  # after the first mixing step of the last module
+            first_hip = tr.dds_get_params(0)
+        k0 = 2 * (K - 1) - t
+        if 0 <= k0 < K:
+            hip[k0] = [tr.dds_get_params_replica(k0, s) for s in range(W)]
     tr.close()
+    # module 0 had not received a gradient at iteration K-1: bit-exact initial weights
+    if K > 1:
+        assert np.array_equal(first_hip, np.concatenate([p.ravel() for p in init[0]]))
+
     DT = torch.float64
     mods = [[torch.as_tensor(p, dtype=DT) for p in m] for m in init]
-    losses, grads = [], []
-    for s in range(wl.W):  # every data-group normalises over its own mini-batch
-        x, y = make_batch(wl, seed, 0, s)
-        h = torch.as_tensor(x, dtype=DT)
-        for k0 in range(K - 1):
-            h, _, _ = N.forward(wl.ops[wl.bounds[k0]:wl.bounds[k0 + 1]], mods[k0], h)
-        ops = wl.ops[wl.bounds[K - 1]:]
-        dlog, saved, loss = N.forward(ops, mods[K - 1], h, torch.as_tensor(y, dtype=torch.int64))
-        _, g = N.backward(ops, mods[K - 1], saved, dlog, need_dx=True)
-        losses.append(float(loss))
-        grads.append(g)
-    want_loss = float(np.mean(losses))
-    assert abs(loss_hip - want_loss) <= 2e-2 * abs(want_loss), (loss_hip, want_loss)
-    Pm = np.full((wl.W, wl.W), 1.0 / wl.W) if mixing is None else np.asarray(mixing, dtype=np.float64)
-    init_last = np.concatenate([p.numpy().ravel() for p in mods[K - 1]])
-    wants = []
-    for s in range(wl.W):
-        want = np.concatenate([(p - wl.lr * sum(Pm[s, r] * grads[r][j] for r in range(wl.W))).numpy().ravel()
-                               for j, p in enumerate(mods[K - 1])])
-        wants.append(want)
-        for name, sl in tensor_slices(wl, K - 1):
-            du = np.linalg.norm(want[sl] - init_last[sl])
-            err = np.linalg.norm(last_hip[s][sl] - want[sl])
-            if name in _dead_biases(wl, K - 1):
-                assert err <= 2e-3, (s, name, err)
-                continue
-            nrm = np.linalg.norm(want[sl])
-            if s == 0:
-                print(f"[full] {wl.name} module {K-1} {name}: update-rel {err / max(du, 1e-30):.3e} rel {err / max(nrm, 1e-30):.3e}", flush=True)
-            assert err <= update_tol * du or err <= rel_tol * nrm, (s, name, err, du, nrm)
-    if mixing is not None:  # the disagreement after the first mixing step, layer by layer
-        mean = sum(wants) / wl.W
-        want_delta = max(np.linalg.norm(w[sl] - mean[sl]) for w in wants for _, sl in tensor_slices(wl, K - 1))
-        assert abs(delta_hip - want_delta) <= 0.1 * want_delta, (delta_hip, want_delta)
-    else:
-        assert delta_hip == 0.0
-    # module 0 has not received a gradient yet: bit-exact initial weights
-    assert np.array_equal(first_hip, np.concatenate([p.ravel() for p in init[0]]))
+    Pm = np.full((W, W), 1.0 / W) if mixing is None else np.asarray(mixing, dtype=np.float64)
+    finit = flat_init(wl, seed)
+    skip = set().union(*[_dead_biases(wl, k0) for k0 in range(K)])
+    modes = [("exact", None)] + ([("rounded", bf16_round())] if wl.precision == "bf16" else [])
+    for mode, q in modes:
+        key = (wl.name, wl.precision, wl.B, seed, mode)
+        if key not in _ORACLE:
+            grads, losses = [], []
+            for s in range(W):  # every data-group normalises over its own mini-batch
+                x, y = make_batch(wl, seed, 0, s)
+                g, loss = fdg.definition_gradient(wl.ops, wl.bounds, mods, x, y, q=q)
+                grads.append(g)
+                losses.append(float(loss))
+                print(f"[full]   oracle ({mode}) data-group {s} done", flush=True)
+            _ORACLE[key] = (grads, losses)
+        grads, losses = _ORACLE[key]
+        want_loss = float(np.mean(losses))
+        loss_tol = 2e-2 if mode == "exact" and wl.precision == "bf16" else 5e-3 if mode == "rounded" else 1e-3
+        assert abs(loss_hip - want_loss) <= loss_tol * abs(want_loss), (mode, loss_hip, want_loss)
+        # update (a)/(b) of Section 3.3 from w(0): w_s = sum_r P[s][r] (w(0) - lr g_r)
+        wants = [[np.concatenate([(p - wl.lr * sum(Pm[s, r] * grads[r][k0][j] for r in range(W))).numpy().ravel()
+                                  for j, p in enumerate(mods[k0])]) for k0 in range(K)] for s in range(W)]
+        for s in range(W if mixing is not None else 1):
+            got = [hip[k0][s] for k0 in range(K)]
+            if mode == "exact":
+                ut = exact_update_tol if exact_update_tol is not None else UPDATE_TOL[wl.precision]
+                et = ELEM_TOL_F32 if wl.precision == "f32" else None
+            else:
+                ut, et = UPDATE_TOL_ROUNDED, ELEM_TOL_ROUNDED
+            check_parity(wl, [got], [wants[s]], finit, tol=None, update_tol=ut, elem_tol=et,
+                         label=f" {mode} first-update group {s}", verbose=(s == 0), skip=skip)
+            for k0 in range(K):  # parameters with an identically zero gradient: absolute bound
+                for name, sl in tensor_slices(wl, k0):
+                    if name in _dead_biases(wl, k0):
+                        assert np.linalg.norm(got[k0][sl] - wants[s][k0][sl]) <= 2e-3, (s, k0, name)
+        if mode == "exact":
+            if mixing is not None:  # the disagreement after the first mixing step (only the last module has moved)
+                mean = sum(wants[s][K - 1] for s in range(W)) / W
+                layers = {}  # a layer's weight vector = its weight and bias together
+                for name, sl in tensor_slices(wl, K - 1):
+                    layers.setdefault(name.rsplit(".", 1)[0], []).append(sl)
+                want_delta = max(np.sqrt(sum(np.sum((wants[s][K - 1][sl] - mean[sl]) ** 2) for sl in sls))
+                                 for s in range(W) for sls in layers.values())
+                assert abs(delta_hip - want_delta) <= 0.1 * want_delta, (delta_hip, want_delta)
+            else:
+                assert delta_hip == 0.0
+
+
+def test_cfg2_full_size_first_update_of_every_module():
+    _first_updates(workload("cfg2_resnet18"), seed=3)
+
+
+def test_cfg1_full_size_first_update_of_every_module():
+    _first_updates(workload("cfg1_cnn"), seed=6)
 
 
 def test_cfg2_full_size_ring_mixing_first_update():
-    _first_update(workload("cfg2_resnet18"), seed=4, mixing=ring_mixing(4, 0.3), update_tol=1.5e-1, rel_tol=0.0)
+    _first_updates(workload("cfg2_resnet18"), seed=3, mixing=ring_mixing(4, 0.3))
 
 
 def test_cfg2_bn_full_size_first_update_fp32_arithmetic():
-    # the same shapes in fp32: every tensor within the update guard, i.e. what the bf16 run below loses is rounding
-    _first_update(workload("cfg2_resnet18_bn", precision="f32"), seed=5, mixing=None, update_tol=2e-2, rel_tol=0.0)
+    # the same shapes in fp32: every tensor within the fp32 update guard of the exact oracle
+    _first_updates(workload("cfg2_resnet18_bn", precision="f32"), seed=5)
 
 
 def test_cfg2_bn_full_size_first_update():
-    # bf16 with normalisation: ReLU decisions behind a bf16-quantised normalisation input differ from the fp64
-    # oracle's for a fraction of a percent of the elements (see test_gpu_batchnorm.py), which moves upstream
-    # gradients by up to ~16 % here; per tensor, the update guard or the stated bar relative to the parameter
-    _first_update(workload("cfg2_resnet18_bn"), seed=5, mixing=None, update_tol=2.5e-1, rel_tol=2e-2)
+    # bf16 with normalisation: ReLU decisions behind a bf16-stored normalisation input differ from the exact
+    # oracle's for a fraction of a percent of the elements, which moves upstream gradients by percents (pinned in
+    # tests/test_oracle_network.py), so against the exact oracle single tensors are only held to 0.3; the
+    # storage-rounding mode takes the same decisions and is held to the tight guard
+    _first_updates(workload("cfg2_resnet18_bn"), seed=5, exact_update_tol=3e-1)
 
 
 def test_cfg2_full_size_long_run_properties():

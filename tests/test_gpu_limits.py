@@ -7,18 +7,17 @@ import pytest
 
 from dds_inputs import make_batch, make_params
 from dds_inputs.configs import tiny_mlp, tiny_resnet
-from parity import flat_init, rel_errors, run_hip, run_oracle
+from parity import check_parity, flat_init, run_hip, run_oracle, thresholds
 
 pytestmark = pytest.mark.gpu
 
 
-def _check(wl, seed, T, tol=1e-4, **kw):
+def _check(wl, seed, T, **kw):
     hip, hl = run_hip(wl, seed, T, every_step=True, **kw)
     orc, ol = run_oracle(wl, seed, T, every_step=True, **kw)
     init = flat_init(wl, seed)
-    for hp, op in zip(hip, orc):
-        for k0, name, rel in rel_errors(wl, hp, op, init)[0]:
-            assert rel <= tol, (k0, name, rel)
+    (_, th), = thresholds("f32", tiny=True)
+    check_parity(wl, hip, orc, init, label=" limits", **th)
     for a, b in zip(hl, ol):
         assert (a is None) == (b is None)
         if a is not None:

@@ -23,15 +23,19 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(P.lib, name), name
 
 
+def _sched_row(rec):
+    """The oracle's schedule record in the order of dds_schedule's DDS_SCHED_INTS integers."""
+    return [rec[k] for k in ("f", "b", "ring_depth", "fwd_slot", "bwd_slot", "err_read", "err_write", "label_slot",
+                             "in_fwd_slot", "in_bwd_slot", "label_bwd_slot", "snap_write", "label_write")]
+
+
 @pytest.mark.parametrize("K", range(1, 9))
 def test_schedule_is_bit_exact_against_the_oracle(K):
     for t in range(64):
         got = P.dds_schedule(K, None, t)
         for rec in fdg.schedule(t, K):
             k0 = rec["k0"]
-            want = [rec["f"], rec["b"], rec["ring_depth"], rec["fwd_slot"], rec["bwd_slot"],
-                    rec["err_read"], rec["err_write"], rec["label_slot"]]
-            assert got[k0].tolist() == want, (K, t, k0)
+            assert got[k0].tolist() == _sched_row(rec), (K, t, k0)
 
 
 @pytest.mark.parametrize("K,d", [(3, [4, 2, 0]), (3, [3, 1, 0]), (4, [5, 4, 2, 1]), (2, [3, 1])])
@@ -40,9 +44,7 @@ def test_schedule_with_custom_delays(K, d):
         got = P.dds_schedule(K, d, t)
         for rec in fdg.schedule(t, K, d):
             k0 = rec["k0"]
-            want = [rec["f"], rec["b"], rec["ring_depth"], rec["fwd_slot"], rec["bwd_slot"],
-                    rec["err_read"], rec["err_write"], rec["label_slot"]]
-            assert got[k0].tolist() == want
+            assert got[k0].tolist() == _sched_row(rec), (K, d, t, k0)
 
 
 def test_schedule_rejects_acausal_delays():

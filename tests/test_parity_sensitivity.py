@@ -1,0 +1,83 @@
+"""The comparison itself under test (CPU only): deliberately wrong variants of the method, computed by the
+oracle with a planted mistake, are pushed through tests/parity.py's check_parity in the place of the HIP
+trajectory, with the threshold sets the GPU parity tests use, at their benchmark-shape settings. Every
+threshold set must reject
+
+  * a run that never updates a weight,
+  * a run that back-propagates through a module's CURRENT weights instead of the weights of the mini-batch's
+    forward pass (Section 3.2 "Backward": the weights of iteration t-2K+2k; the definition W~_s(tau) of
+    Section 3.3) -- the mistake a decoupled implementation is most likely to make,
+  * the correct trajectory with ONE element of one tensor displaced by three times the rms update (what a
+    tile-edge or pad-lane error looks like to a norm: nothing),
+
+and must accept the correct trajectory perturbed at rounding level."""
+import numpy as np
+import pytest
+
+from dds_inputs import workload
+from dds_inputs.configs import tiny_resnet
+from oracle import fdg
+from parity import bf16_round, check_parity, flat_init, run_oracle, thresholds
+
+
+class CurrentWeightsPipeline(fdg.Pipeline):
+    """Planted mistake: the backward pass of every in-flight mini-batch sees the weights the module holds
+    now, not the ones its forward pass used."""
+
+    def step(self, batches):
+        for s in range(self.S):
+            for k0 in range(self.K):
+                for b, (saved, _, out) in list(self.inflight[s][k0].items()):
+                    self.inflight[s][k0][b] = (saved, self.w[s][k0], out)
+        return super().step(batches)
+
+
+def _rejected(wl, got, want, init, kw):
+    try:
+        check_parity(wl, got, want, init, verbose=False, **kw)
+    except AssertionError:
+        return True
+    return False
+
+
+CASES = [
+    # (workload, T, tiny): the settings of the GPU tests of the same name
+    ("cfg2_resnet18 B=4 bf16", lambda: workload("cfg2_resnet18", B=4), 16, False),
+    ("cfg1_cnn B=8 fp32", lambda: workload("cfg1_cnn", B=8), 16, False),
+    # K = 8 chain of the narrow residual net; two data-groups instead of eight keep the CPU suite short
+    ("cfg3_resnet56 B=2 W=2 bf16", lambda: workload("cfg3_resnet56", B=2, W=2), 20, False),
+    ("tiny_resnet fp32", lambda: tiny_resnet(K=3, W=2, B=4), 10, True),
+]
+
+
+@pytest.mark.parametrize("name,make,T,tiny", CASES, ids=[c[0] for c in CASES])
+def test_threshold_sets_reject_wrong_methods_and_single_element_errors(name, make, T, tiny):
+    wl = make()
+    seed = 0
+    init = flat_init(wl, seed)
+    # the mode the bug would live in: a bf16 implementation rounds where the library rounds
+    q = bf16_round() if wl.precision == "bf16" else None
+    truth = {}
+    for mode, kw in thresholds(wl.precision, tiny):
+        if wl.precision == "bf16" and mode == "exact":
+            continue  # the loose guard against the exact oracle is not the assertion that carries the load
+        truth[mode] = (run_oracle(wl, seed, T, q=q if mode == "rounded" else None)[0], kw)
+    stale_bug = run_oracle(wl, seed, T, q=q, pipeline_cls=CurrentWeightsPipeline)[0]
+    never = [[p.copy() for p in init]]
+    for mode, (want, kw) in truth.items():
+        assert _rejected(wl, never, want, init, kw), f"{name}/{mode}: a run without updates passes"
+        assert _rejected(wl, stale_bug, want, init, kw), f"{name}/{mode}: back-propagating through current weights passes"
+        _, worst_u, worst_e = check_parity(wl, stale_bug, want, init, tol=None, update_tol=None, elem_tol=None, verbose=False)
+        print(f"[sensitivity] {name}/{mode}: current-weights variant scores update-rel {worst_u:.3e}, "
+              f"max-elem/rms-update {worst_e:.3e} (bounds {kw['update_tol']}, {kw['elem_tol']})")
+        # one displaced element in the largest tensor of module 0
+        rng = np.random.default_rng(1)
+        one = [p.copy() for p in want[-1]]
+        big = int(np.argmax([p.size for p in one]))
+        upd = one[big] - init[big]
+        i = int(rng.integers(one[big].size))
+        one[big][i] += 3.0 * np.sqrt(np.mean(upd ** 2))
+        assert _rejected(wl, [one], [want[-1]], init, kw), f"{name}/{mode}: one displaced element passes"
+        # rounding-level noise on the correct trajectory is accepted
+        ok = [p + 1e-7 * np.abs(p) * rng.standard_normal(p.size) for p in want[-1]]
+        check_parity(wl, [ok], [want[-1]], init, verbose=False, **kw)
