@@ -27,7 +27,7 @@ def _compare(wl, seed, T, delays=None, every_step=False, lr_schedule=None, tiny=
         orc, ol = run_oracle(wl, seed, T, delays, every_step, lr_schedule, q=bf16_round() if mode == "rounded" else None)
         w = check_parity(wl, hip, orc, init, label=" " + mode, **kw)
         worst = w[0] if worst is None else worst
-        loss_tol = 10 * kw["tol"] if mode == "exact" else 5e-3
+        loss_tol = 10 * kw["tol"]
         for t, (a, b) in enumerate(zip(hl, ol)):
             assert (a is None) == (b is None), f"loss availability differs at t={t}"
             if a is not None:

@@ -174,8 +174,9 @@ def test_snapshot_ring_slots_hold_the_weights_of_the_scheduled_iteration(K, dela
             k0 = rec["k0"]
             versions[k0].append(tr.dds_get_params(k0))
             if rec["b"] >= 0:
-                # what this iteration's backward read: the slot must hold the weights of iteration t - 2d
-                assert held[k0][rec["bwd_slot"]] == t - 2 * d[k0], (t, k0)
+                # what this iteration's backward read: the slot must hold the weights of iteration t - 2d (an
+                # earlier version number with the same content while no update had happened yet)
+                assert np.array_equal(versions[k0][held[k0][rec["bwd_slot"]]], versions[k0][t - 2 * d[k0]]), (t, k0)
                 held[k0][rec["snap_write"]] = t + 1
             else:
                 assert np.array_equal(versions[k0][-1], versions[k0][0]), (t, k0)
