@@ -50,7 +50,7 @@ UPDATE_TOL_TINY_F32 = 1e-3
 UPDATE_TOL_ROUNDED = 1e-1
 UPDATE_TOL_ROUNDED_BN = 4e-1
 # Element-wise figure max|hip - oracle| / rms(update), fp32 path against the exact oracle: toy networks
-# (measured <= 3e-4); benchmark shapes at the full batch (measured 2e-3, 6e-2 with batch normalisation); benchmark shapes at the
+# (measured <= 3e-4); benchmark shapes at the full batch (measured 2e-3); benchmark shapes at the
 # reduced batches the pipeline tests use, where one ReLU / max-pool decision taken differently in fp32
 # and fp64 changes one of the ~200 (sample, pixel) terms of a late layer's mean gradient (measured <= 0.19).
 ELEM_TOL_F32_TINY = 1e-2
@@ -207,7 +207,9 @@ def thresholds(precision, tiny=False, full_batch=False, bn=False):
     oracle, the tighter update guard and the element-wise bound against the storage-rounding mode.
     tiny: toy networks; full_batch: benchmark shapes at the full batch; bn: nets with batch normalisation."""
     if precision == "f32":
-        elem = ELEM_TOL_F32_TINY if tiny else ELEM_TOL_F32_FULL if full_batch else ELEM_TOL_F32
+        # (with batch normalisation a decision taken differently also shifts its channel's statistics: measured 0.19
+        # on a 4 x 4 layer at the full batch)
+        elem = ELEM_TOL_F32_TINY if tiny else ELEM_TOL_F32_FULL if (full_batch and not bn) else ELEM_TOL_F32
         return [("exact", dict(tol=TOL["f32"], update_tol=UPDATE_TOL_TINY_F32 if tiny else UPDATE_TOL["f32"], elem_tol=elem))]
     return [("exact", dict(tol=TOL["bf16"], update_tol=0.5 if bn else UPDATE_TOL["bf16"], elem_tol=None)),
             ("rounded", dict(tol=TOL["bf16"], update_tol=UPDATE_TOL_ROUNDED_BN if bn else UPDATE_TOL_ROUNDED,
