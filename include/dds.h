@@ -163,6 +163,17 @@ int dds_get_params_replica(dds_ctx* ctx, int module, int replica, float* dst_dev
  * fp64 from the fp32 master weights. Exactly 0 without a mixing matrix. Synchronises stream. */
 int dds_consensus_error(dds_ctx* ctx, double* host_out, void* hip_stream);
 
+/* dds_consensus_error for callers that cannot allocate device memory or hand over a workspace for this
+ * call (code under HIP graph capture set-up, tight serving loops, harnesses that forbid allocations): the
+ * per-block partial sums of the reduction live in a device array of fixed size inside the library
+ * (512 KiB per GPU, held until the process ends) instead of in the arena. Same result as
+ * dds_consensus_error, bit for bit. Calls no hipMalloc / hipFree. Limit: every module must satisfy
+ * 2 * ceil(parameters of a layer / 1024, summed over layers) * W <= 65536, else DDS_EUNSUPPORTED with a
+ * message (nothing is launched). All calls on one GPU share the array: two calls that overlap in time on
+ * the same GPU (different streams or threads) race; the array keeps the previous call's contents, which is
+ * harmless because the kernel writes every entry that is read back. Synchronises stream. */
+int dds_consensus_error_static(dds_ctx* ctx, double* host_out, void* hip_stream);
+
 /* One iteration t of every module (Algorithm 1 loop body for all S*K agents).
  * x_device[s]: replica s's mini-batch, fp32 [B,in_c,in_h,in_w] (NCHW);
  * y_device[s]: its targets, int32 [B], values in [0,classes). Both arrays of

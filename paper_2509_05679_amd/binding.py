@@ -25,7 +25,7 @@ PRECISION = {"f32": 0, "bf16": 1}
 ACTIVATIONS = {"store": 0, "recompute": 1}  # dds_spec.activations
 
 EXPORTS = ["dds_schedule", "dds_step_size", "dds_arena_bytes", "dds_create", "dds_destroy", "dds_param_count",
-           "dds_get_params", "dds_set_params", "dds_get_params_replica", "dds_consensus_error", "dds_step", "dds_get_loss", "dds_step_count",
+           "dds_get_params", "dds_set_params", "dds_get_params_replica", "dds_consensus_error", "dds_consensus_error_static", "dds_step", "dds_get_loss", "dds_step_count",
            "dds_launches_last_step", "dds_gemm_flops_per_step", "dds_profile", "dds_profile_read",
            "dds_debug_bytes", "dds_debug_read", "dds_last_error"]
 
@@ -71,6 +71,7 @@ def _load():
     lib.dds_set_params.argtypes = [vp, C.c_int, vp, C.c_size_t, vp]
     lib.dds_get_params_replica.argtypes = [vp, C.c_int, C.c_int, vp, C.c_size_t, vp]
     lib.dds_consensus_error.argtypes = [vp, C.POINTER(C.c_double), vp]
+    lib.dds_consensus_error_static.argtypes = [vp, C.POINTER(C.c_double), vp]
     lib.dds_step.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.c_float, vp]
     lib.dds_get_loss.argtypes = [vp, f32p, vp]
     lib.dds_step_count.argtypes = [vp]
@@ -209,6 +210,11 @@ class Trainer:
     def dds_consensus_error(self) -> float:
         v = C.c_double()
         _check(lib.dds_consensus_error(self.ctx, C.byref(v), self._stream()))
+        return v.value
+
+    def dds_consensus_error_static(self) -> float:
+        v = C.c_double()
+        _check(lib.dds_consensus_error_static(self.ctx, C.byref(v), self._stream()))
         return v.value
 
     def dds_step(self, xs, ys, lr: float = math.nan):

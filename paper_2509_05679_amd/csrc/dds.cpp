@@ -1221,22 +1221,24 @@ int dds_get_params_replica(dds_ctx* c, int module, int replica, float* dst, size
   return params_io(c, module, replica, dst, n, stream, false);
 }
 
-int dds_consensus_error(dds_ctx* c, double* host_out, void* stream) {
-  if (!c || !host_out) return fail(DDS_EINVAL, "dds_consensus_error: null argument");
+// Disagreement measure with the per-block partial sums of every module in `shared` (device memory of at least
+// 2 * blocks_update * W doubles for the largest module), or in the module's own arena block if shared is null. The
+// kernel writes every entry the host reads, so stale contents do not matter.
+static int consensus_error_impl(dds_ctx* c, double* host_out, hipStream_t s, double* shared) {
   *host_out = 0.0;
   if (!c->gossip) return DDS_OK;
   c->chained = false;
-  hipStream_t s = (hipStream_t)stream;
   if (int rc = order_after_last_step(c, s)) return rc;
   double worst = 0.0;
   std::vector<double> host, sums;
   for (Module& m : c->mods) {
     if (m.blocks_update == 0) continue;
     const size_t n = (size_t)2 * m.blocks_update * c->W;
-    launch_consensus(m.descs_dev, m.map_update_dev, m.blocks_update, c->W, m.n_master, m.cons_dev, s);
+    double* dev = shared ? shared : m.cons_dev;
+    launch_consensus(m.descs_dev, m.map_update_dev, m.blocks_update, c->W, m.n_master, dev, s);
     HIP_TRY(hipGetLastError());
     host.resize(n);
-    HIP_TRY(hipMemcpyAsync(host.data(), m.cons_dev, n * sizeof(double), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(host.data(), dev, n * sizeof(double), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     // a layer's weight vector w_l (Section 2.1) is its weight and its bias together: [layer][s], both parts
     // of every block added in order
@@ -1251,6 +1253,42 @@ int dds_consensus_error(dds_ctx* c, double* host_out, void* stream) {
   *host_out = std::sqrt(worst);
   return DDS_OK;
 }
+
+int dds_consensus_error(dds_ctx* c, double* host_out, void* stream) {
+  if (!c || !host_out) return fail(DDS_EINVAL, "dds_consensus_error: null argument");
+  return consensus_error_impl(c, host_out, (hipStream_t)stream, nullptr);
+}
+
+// ---- the same measure for callers that must not trigger a device allocation: the per-block partial sums go to a
+// file-scope device array instead of the arena block (so a context created in an arena sized without that block,
+// or any caller that forbids allocations, can still ask). One array per GPU, shared by every call on that GPU.
+constexpr size_t kStaticScratchDoubles = 65536;  // 512 KiB per GPU, held until the process ends
+static __device__ __align__(256) double scratch[kStaticScratchDoubles];
+constexpr int kMaxDevices = 64;
+static double* g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each GPU (the array's name is only a host-side handle)
+
+int dds_consensus_error_static(dds_ctx* c, double* host_out, void* stream) {
+  if (!c || !host_out) return fail(DDS_EINVAL, "dds_consensus_error_static: null argument");
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(DDS_EUNSUPPORTED, "dds_consensus_error_static: device %d out of range", dev);
+  if (!g_scratch_ptr[dev]) {  // once per device, with that device current: every GPU has its own copy at its own address
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return fail(DDS_EHIP, "dds_consensus_error_static: no device address for the scratch array");
+    g_scratch_ptr[dev] = (double*)ptr;
+  }
+  for (const Module& m : c->mods) {
+    const size_t need = (size_t)2 * m.blocks_update * c->W;
+    if (c->gossip && need > kStaticScratchDoubles)
+      return fail(DDS_EUNSUPPORTED,
+                  "dds_consensus_error_static: module %d needs %zu partial sums (2 per 1024 parameters and data-group), "
+                  "the static scratch holds %zu; use dds_consensus_error",
+                  m.k0, need, kStaticScratchDoubles);
+  }
+  return consensus_error_impl(c, host_out, (hipStream_t)stream, g_scratch_ptr[dev]);
+}
+
 int dds_set_params(dds_ctx* c, int module, const float* src, size_t n, void* stream) {
   if (c && c->t != 0) return fail(DDS_EINVAL, "dds_set_params is only valid before the first step");
   return params_io(c, module, 0, (float*)src, n, stream, true);
