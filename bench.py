@@ -53,7 +53,9 @@ def cpu_baseline(wl, seconds_budget=20.0):
     import torch
     from dds_inputs import make_batch, make_params, workload
     from oracle import fdg
-    small_b = {"cfg0_mlp": wl.B, "cfg1_cnn": 8, "cfg2_resnet18": 2, "cfg3_resnet56": 2, "cfg4_resnet34w": 1}.get(wl.name, 2)
+    # per-group batch of the sample: large enough that per-sample cost is close to the full shape's (measured on
+    # the ResNet-18 configuration: 17.7 samples/s at batch 2, ~20 at batch 16), small enough for ~20-30 s in all
+    small_b = {"cfg0_mlp": wl.B, "cfg1_cnn": 32, "cfg2_resnet18": 16, "cfg3_resnet56": 4, "cfg4_resnet34w": 1}.get(wl.name, 2)
     small = workload(wl.name, B=small_b)
     pipe = fdg.Pipeline(small.ops, small.bounds, small.W, make_params(small, 0), small.lr, small.momentum)
     pipe.keep_history = False
@@ -85,6 +87,9 @@ def main():
     ap.add_argument("--workload", default="cfg2_resnet18")
     ap.add_argument("--batch", type=int, default=None, help="override per-replica batch (debug only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a 1 GiB device-to-device tensor copy, five times (the kernel of known size that the "
+                         "FETCH_SIZE / WRITE_SIZE counters of the rocprofv3 summaries under profiles/ are scaled by)")
     ap.add_argument("--activations", default="store", choices=["store", "recompute"],
                     help="what delayed modules keep between forward and backward: every saved tensor (default) or "
                          "input, output and a parameter snapshot, with a second forward pass before the backward")
@@ -98,6 +103,15 @@ def main():
         sys.exit(2)
 
     import torch
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": "5 copies of 1 GiB (elementwise copy kernel: 1 GiB read + 1 GiB written each)"}))
+        return
     import paper_2509_05679_amd as P
     from dds_inputs import make_batch, make_params, workload
 
@@ -143,7 +157,8 @@ def main():
     hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1)
     ms_per_step = ms.value / args.steps
     loss = tr.dds_get_loss()
-    # four more regions of the same length, for the spread only: `value` is the region above
+    # four more regions of the same length: `value` is the median region of the five
+    first_region = ms_per_step
     runs = [ms_per_step]
     for r in range(4):
         hip.hipEventRecord(e0, sp)
@@ -153,6 +168,7 @@ def main():
         hip.hipEventSynchronize(e1)
         hip.hipEventElapsedTime(ctypes.byref(ms), e0, e1)
         runs.append(ms.value / args.steps)
+    ms_per_step = sorted(runs)[2]
     samples = wl.W * wl.B
     flops = tr.dds_gemm_flops_per_step()
     launches = tr.dds_launches_last_step()
@@ -214,7 +230,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: K={wl.K} modules, W={wl.W} replicas x batch {wl.B}, {wl.precision}",
                    "launches_per_step": launches, "wall_ms_per_step": wall * 1e3 / args.steps,
-                   "ms_per_step_of_5_regions": [round(v, 4) for v in runs], "median_ms_per_step": sorted(runs)[2],
+                   "ms_per_step_of_5_regions": [round(v, 4) for v in runs], "first_region_ms_per_step": first_region,
+                   "value_is": "median of five timed regions of `steps` consecutive steady-state steps each",
                    "loss_after": loss, "arena_GiB": tr.arena_bytes / 2 ** 30, "mixing": args.mixing, "activations": args.activations,
                    "consensus_error": tr.dds_consensus_error() if mixing is not None else 0.0},
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": peak, "unit": "TFLOP/s",

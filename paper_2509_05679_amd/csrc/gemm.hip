@@ -6,6 +6,8 @@
 // with one 16-byte LDS read per operand fragment. Lanes 0-31 read the first 16
 // bytes of a 32-byte k-step and lanes 32-63 the second, for A and B alike, so the
 // pairing of k indices inside an instruction is consistent by construction.
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace dds {
@@ -1179,6 +1181,7 @@ struct WgradGeom {
   int cblocks;     // 64-channel blocks of the real input tensor
   int sub[4];      // S2: sub-pixel (dy * 2 + dx) served by blockIdx.y / cblocks
   int rmap[2][2];  // S2: real kernel row for (virtual row R', dy), -1 if none; the same table serves columns
+  int xcd_remap;   // splits are a multiple of eight: workgroups of one split are dealt to one XCD (see the kernel)
 };
 
 // S2 = false: 3x3, stride 1, pad 1 (nine taps, TW x TH tiles of the image itself).
@@ -1220,10 +1223,25 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wave_m = wave & 1, wave_n = (wave >> 1) & 1;
   const int tg = wave >> 2;  // tap group: kernel row of this wave's three taps (stride 1)
-  const int k0 = blockIdx.x * 64, z = blockIdx.z;
-  const int sub = S2 ? wg.sub[blockIdx.y / wg.cblocks] : 0;
+  // Workgroup -> (k-block, sub-pixel / c-block, split). Every (k, c) block of one split reads the same dY rows and
+  // X patches, so they should meet in one L2: workgroups are handed to the eight XCDs round-robin in launch order,
+  // hence launch index i lands on XCD i % 8 as the (i / 8)-th workgroup of that XCD. With a split count that is
+  // a multiple of eight, XCD x takes the splits z = x (mod 8) and runs all blocks of a split back to back, so
+  // they are resident together and walk the pixel tiles at the same pace.
+  int bx = blockIdx.x, by = blockIdx.y, z = blockIdx.z;
+  if (wg.xcd_remap) {
+    const int nblk = gridDim.x * gridDim.y;
+    const int lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int xcd = lin & 7, j = lin >> 3;
+    const int blk = j % nblk;
+    z = (j / nblk) * 8 + xcd;
+    bx = blk % gridDim.x;
+    by = blk / gridDim.x;
+  }
+  const int k0 = bx * 64;
+  const int sub = S2 ? wg.sub[by / wg.cblocks] : 0;
   const int sdy = sub >> 1, sdx = sub & 1;
-  const int c0 = (S2 ? blockIdx.y % wg.cblocks : blockIdx.y) * 64;
+  const int c0 = (S2 ? by % wg.cblocks : by) * 64;
   // Split z = (data-group, j): the data-group's tiles are dealt to its q splits as evenly as whole
   // tiles allow (tile counts differ by at most one), so a split never mixes two data-groups.
   const int q = p.nsplit / p.nrep, rep_tiles = (p.P >> 7) / p.nrep;
@@ -1375,7 +1393,7 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
 #pragma unroll
       for (int tap = 0; tap < NT; ++tap)
         if (!S2 || live[tap]) mfma16B<bf16_t>(af[ks & 1], bf[ks & 1][tap], acc[tap]);
-      if (wave_n == 0 && blockIdx.y == 0 && tg == (S2 ? 0 : 1)) mfma16B<bf16_t>(af[ks & 1], ones, accb);  // bias gradient: column sums of dY
+      if (wave_n == 0 && by == 0 && tg == (S2 ? 0 : 1)) mfma16B<bf16_t>(af[ks & 1], ones, accb);  // bias gradient: column sums of dY
     }
   }
   wait_vm<0>();
@@ -1391,7 +1409,7 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
       for (int tap = 0; tap < NT; ++tap)
         if (live[tap]) out[(size_t)k * p.NK + tapreal[tap] * p.Cx + cin] = p.alpha * acc[tap][e];
     }
-    if (wave_n == 0 && (lane & 31) == 0 && blockIdx.y == 0 && tg == (S2 ? 0 : 1)) out[(size_t)p.Mout * p.NK + k] = p.alpha * accb[e];
+    if (wave_n == 0 && (lane & 31) == 0 && by == 0 && tg == (S2 ? 0 : 1)) out[(size_t)p.Mout * p.NK + k] = p.alpha * accb[e];
   }
 }
 
@@ -1522,6 +1540,7 @@ bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
   WgradGeom wg{};
   wg.tiles_h = tiles_h;
   wg.cblocks = cblocks;
+  wg.xcd_remap = (p.nsplit % 8 == 0 && getenv("DDS_NO_XCD_REMAP") == nullptr) ? 1 : 0;
   int nsub = 1;
   if (s2) {
     // real tap for (virtual tap, sub-pixel offset): 3x3 pad 1: rows 2oy-1, 2oy, 2oy+1; 1x1 pad 0: row 2oy
@@ -1591,6 +1610,9 @@ int wgrad_choose_split(int dt, const WgradParams& shape, int W, int target_wgs) 
     if (wgrad_dma_eligible(probe, &nsub, &cblocks)) {
       const int blocks = cdiv(Mout, 64) * nsub * cblocks;
       const int rep_tiles = per_replica / 128;
+      // a stride-2 workgroup has four waves where a stride-1 one has twelve, and the four sub-pixels of a 3x3
+      // kernel carry 4 : 2 : 2 : 1 taps: more, smaller workgroups fill the chip and even out (DDS_S2_SPLIT_FACTOR)
+      if (shape.stride == 2) { int f = 4; if (const char* e = getenv("DDS_S2_SPLIT_FACTOR")) f = atoi(e); target_wgs *= f > 0 ? f : 1; }
       int q = cdiv(target_wgs, blocks * W);
       if (q > rep_tiles) q = rep_tiles;
       if (q * W > 256) q = 256 / W;
