@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdds.so")
-SOURCES = ["dds.cpp", "gemm.hip", "misc.hip", "norm.hip"]
+SOURCES = ["dds.cpp", "gemm.hip", "misc.hip", "norm.hip", "narrow.hip"]
 # -Wno-inline-asm: the global->LDS copy statements list m0 as clobbered (they write it); the compiler warns that m0
 # is a reserved register, which is the point: it must not keep one of its own m0 set-ups alive across them
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",

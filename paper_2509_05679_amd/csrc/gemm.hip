@@ -1466,6 +1466,7 @@ int launch_conv_t(const ConvParams& p, hipStream_t s) {
 template <typename T>
 int launch_conv_one(const ConvParams& p, hipStream_t s) {
   constexpr int BKB = 64;
+  if (sizeof(T) == 2 && launch_conv_narrow(p, s)) return 1;
   if (launch_dma<T>(p, s)) return 1;
   // dgrad of a stride-2 convolution: workgroups per parity class (class (0,0) is the largest)
   const bool s2 = p.dgrad && p.stride == 2 && p.Cx % (BKB / (int)sizeof(T)) == 0 &&
@@ -1540,7 +1541,7 @@ bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
   WgradGeom wg{};
   wg.tiles_h = tiles_h;
   wg.cblocks = cblocks;
-  wg.xcd_remap = (p.nsplit % 8 == 0 && getenv("DDS_NO_XCD_REMAP") == nullptr) ? 1 : 0;
+  wg.xcd_remap = p.nsplit % 8 == 0 ? 1 : 0;
   int nsub = 1;
   if (s2) {
     // real tap for (virtual tap, sub-pixel offset): 3x3 pad 1: rows 2oy-1, 2oy, 2oy+1; 1x1 pad 0: row 2oy
@@ -1568,6 +1569,7 @@ bool launch_wgrad_dma(const WgradParams& p, hipStream_t s) {
 template <typename T>
 int launch_wgrad_t(const WgradParams& p, hipStream_t s) {
   constexpr int CE = 16 / sizeof(T);
+  if (sizeof(T) == 2 && launch_wgrad_narrow(p, s)) return 1;
   if (sizeof(T) == 2 && launch_wgrad_dma(p, s)) return 1;
   if (p.Mout <= 64 && p.NK + CE <= 128) {  // e.g. the stem: 3 input channels, 9 taps
     dim3 grid(cdiv(p.Mout, 64), 1, p.nsplit);
@@ -1596,6 +1598,7 @@ int wgrad_choose_split(int dt, const WgradParams& shape, int W, int target_wgs) 
   const int Mout = shape.Mout, NK = shape.NK, P = shape.P;
   const int per_replica = P / W;  // pixels of one replica's mini-batch
   if (dt != DT_F32) {
+    if (const int n = wgrad_narrow_split(shape, W)) return n;
     // Asynchronous kernel: 64 x 64 output blocks per (sub-pixel, channel block); a data-group's 128-pixel
     // tiles are dealt to its splits. Take the fewest splits that give the launch target_wgs workgroups:
     // the partial sums cost HBM traffic (written here, read by the update) in proportion to the split
@@ -1611,8 +1614,8 @@ int wgrad_choose_split(int dt, const WgradParams& shape, int W, int target_wgs) 
       const int blocks = cdiv(Mout, 64) * nsub * cblocks;
       const int rep_tiles = per_replica / 128;
       // a stride-2 workgroup has four waves where a stride-1 one has twelve, and the four sub-pixels of a 3x3
-      // kernel carry 4 : 2 : 2 : 1 taps: more, smaller workgroups fill the chip and even out (DDS_S2_SPLIT_FACTOR)
-      if (shape.stride == 2) { int f = 4; if (const char* e = getenv("DDS_S2_SPLIT_FACTOR")) f = atoi(e); target_wgs *= f > 0 ? f : 1; }
+      // kernel carry 4 : 2 : 2 : 1 taps: twice the workgroups (2.24 ms per ResNet-18 step; 2.26 with one or four times)
+      if (shape.stride == 2) target_wgs *= 2;
       int q = cdiv(target_wgs, blocks * W);
       if (q > rep_tiles) q = rep_tiles;
       if (q * W > 256) q = 256 / W;

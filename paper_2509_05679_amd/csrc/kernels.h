@@ -134,7 +134,13 @@ struct UpdateDesc {
 // Both return the kernel family that took the launch: 0 = generic implicit GEMM (register-staged),
 // 1 = the asynchronous global->LDS kernels (conv3x3_dma_kernel / wgrad_dma_kernel).
 int launch_conv(int dt, const ConvParams& p, hipStream_t s);
+// bf16 3x3 stride-1 layers with 16-channel rows (narrow.hip); false: not taken, nothing launched
+bool launch_conv_narrow(const ConvParams& p, hipStream_t s);
 int launch_wgrad(int dt, const WgradParams& p, hipStream_t s);
+// bf16 3x3 stride-1 layers with 16-channel rows (narrow.hip): the split count such a layer gets (0: not its), and
+// the launch (false: not taken, nothing launched)
+int wgrad_narrow_split(const WgradParams& shape, int W);
+bool launch_wgrad_narrow(const WgradParams& p, hipStream_t s);
 // Chooses the split count of the pixel reduction for a wgrad problem: a multiple of the replica
 // count W, so that no split mixes two replicas. shape: every field that describes the layer
 // (Nimg, H, W, Cx, Ho, Wo, Mout, ldy, R, S, stride, pad, NK, P, zeros non-null); nsplit,

@@ -89,6 +89,12 @@ def test_isolated_data_groups_identity_matrix_fp32():
     _compare(wl, seed=14, T=8, mixing=eye)
 
 
+def test_ring_of_four_sixteen_channel_layers_bf16():
+    # the narrow-layer kernels with every data-group's own weights in one launch (weights picked per wave)
+    wl = tiny_resnet(K=2, W=4, B=4, hw=16, c=16, precision="bf16")
+    _compare(wl, seed=18, T=8, mixing=ring_mixing(4, 0.3), tiny=False)
+
+
 def test_complete_graph_reproduces_exact_mean_path():
     """P = (1/W) 11^T through the per-data-group code must land on the single-copy hot path."""
     import torch

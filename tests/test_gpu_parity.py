@@ -94,6 +94,14 @@ def test_cfg3_resnet56_reduced_batch_bf16():
     _compare(wl, seed=0, T=2 * (wl.K - 1) + 6)
 
 
+def test_sixteen_channel_layers_bf16():
+    # 16 x 16 images, 16 channels: the first block runs on the narrow-layer kernels (direct 16-channel forward /
+    # dgrad with sign plane, residual and shortcut-gradient epilogues; 16-channel weight gradient); W = 3 data-groups
+    # and batch 5 leave ragged workgroups
+    _compare(tiny_resnet(K=2, W=3, B=5, hw=16, c=16, precision="bf16"), seed=8, T=8, every_step=True)
+    _compare(tiny_resnet(K=1, W=1, B=1, hw=16, c=16, precision="bf16"), seed=9, T=3, every_step=True)
+
+
 def test_odd_shapes_fp32_and_bf16():
     # 7 x 9 images, batch 3, stride-2 projection block (parity classes of unequal size, shortcut
     # folded into the dgrad), a conv with 10 output channels (padded channel stride)
