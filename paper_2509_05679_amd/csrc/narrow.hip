@@ -289,6 +289,8 @@ int wgrad_narrow_split(const WgradParams& shape, int W) {
   const int rows_rep = (shape.Nimg / W) * shape.H;
   const int CH = 256 / shape.W;
   // about a thousand workgroups (four a CU), at least one chunk each
+  // (measured on the ResNet-56 configuration: 256 / 512 / 1024 / 2048 workgroups -> 2.94 / 2.84 / 2.79 / 2.86 ms per
+  // step; the update kernel reads one partial row per split, which is what more splits cost)
   int q = (1024 + W - 1) / W;
   const int qmax = rows_rep / CH > 0 ? rows_rep / CH : 1;
   if (q > qmax) q = qmax;
