@@ -100,6 +100,8 @@ def test_sixteen_channel_layers_bf16():
     # and batch 5 leave ragged workgroups
     _compare(tiny_resnet(K=2, W=3, B=5, hw=16, c=16, precision="bf16"), seed=8, T=8, every_step=True)
     _compare(tiny_resnet(K=1, W=1, B=1, hw=16, c=16, precision="bf16"), seed=9, T=3, every_step=True)
+    # 32 x 32 images (two 16-pixel runs per image row); the second and third block are 32 channels wide at 16 x 16
+    _compare(tiny_resnet(K=3, W=2, B=3, hw=32, c=16, precision="bf16"), seed=10, T=8)
 
 
 def test_odd_shapes_fp32_and_bf16():
