@@ -1289,13 +1289,15 @@ __global__ __launch_bounds__(S2 ? 256 : 768) void wgrad_dma_kernel(WgradParams p
     const bool yok = live_t && ycol_ok;
 #pragma unroll
     for (int u = 0; u < FY; ++u) {  // dY rows: tile pixel 8*(wave + NWV u) + l8
-      const bool live = live_t && wave + NWV * u < 16;
+      const bool live = live_t && wave + NWV * u < 16;  // wave-uniform
+      if (RING == 2 && !live) continue;  // only a fixed count of fills per tile (wait_vm<NF>) needs the surplus ones
       dma16(yok && live ? ysrc + (size_t)u * (NWV * 8) * ybytes : zsrc, live ? base + (wave + NWV * u) * 1024 : lds_dump);
     }
 #pragma unroll
     for (int u = 0; u < PF; ++u) {  // patch rows
       const int wl = wave + NWV * u;
-      const bool live = live_t && wl < pw_total;
+      const bool live = live_t && wl < pw_total;  // wave-uniform
+      if (RING == 2 && !live) continue;
       const int gh = h0 + (pflag[u] & 255) - 1;
       const bool ok = live && xcol_ok && (pflag[u] >> 8) && (unsigned)gh < (unsigned)p.Ho;
       dma16(ok ? xsrc + prel[u] : zsrc, live ? base + 16384 + wl * 1024 : lds_dump);
