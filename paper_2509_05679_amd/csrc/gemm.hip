@@ -541,6 +541,8 @@ struct HaloGeom {
   int patch_pix;           // imgs * PP
   int patch_bytes;         // patch_pix * 144 rounded to 256
   int flip;                // dgrad: tap (r,s) reads the patch at (2-r, 2-s)
+  int tpi_log, tilesw_log; // log2 of the tiles per image and per image row (both powers of two)
+  uint32_t mPP, mPW;       // ceil(2^32 / PP), ceil(2^32 / PW): floor(i / d) == __umulhi(i, m) for i, d < 2^16
 };
 
 // ------------------------------------------------------------------ 3x3 stride-1 forward / dgrad, asynchronous LDS fills
@@ -610,9 +612,8 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) =
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // scalar: everything derived from it stays in SGPRs
   const int wave_m = wave % (BM / WM), wave_n = wave / (BM / WM);
-  const int tiles_per_img = g.tiles_w * g.tiles_h;
-  const int grp = blockIdx.x / tiles_per_img, tin = blockIdx.x - grp * tiles_per_img;
-  const int th_idx = tin / g.tiles_w, tw_idx = tin - th_idx * g.tiles_w;
+  const int grp = blockIdx.x >> g.tpi_log, tin = blockIdx.x - (grp << g.tpi_log);
+  const int th_idx = tin >> g.tilesw_log, tw_idx = tin - (th_idx << g.tilesw_log);
   const int img0 = grp * g.imgs, h0 = th_idx << g.th_log, w0 = tw_idx << g.tw_log;
   const int n0 = blockIdx.y * BN;
   if (p.nrep > 1) {  // the launcher made sure that the images of a tile belong to one data-group
@@ -635,8 +636,8 @@ __global__ __launch_bounds__(64 * (BM / WM) * (BN / WN), (BM / WM) * (BN / WN) =
   for (int row = tid; row < prow; row += 64 * NW) {
     int v = -1;
     if (row < g.patch_pix) {
-      const int im = row / g.PP, rem = row - im * g.PP;
-      const int yy = rem / g.PW, xx = rem - yy * g.PW;
+      const int im = (int)__umulhi((uint32_t)row, g.mPP), rem = row - im * g.PP;
+      const int yy = (int)__umulhi((uint32_t)rem, g.mPW), xx = rem - yy * g.PW;
       const int gi = img0 + im, gh = h0 + yy - 1, gw = w0 + xx - 1;
       if (gi < p.Nimg && (unsigned)gh < (unsigned)p.H && (unsigned)gw < (unsigned)p.W)
         v = ((gi * p.H + gh) * p.W + gw) * CPR + patch_swizzle(xx, yy);
@@ -915,6 +916,11 @@ bool halo_geometry(const ConvParams& p, HaloGeom& g, int BM = 256, int chunk_byt
   g.patch_pix = imgs * g.PP;
   g.patch_bytes = (g.patch_pix * 144 + 255) / 256 * 256;
   g.flip = p.dgrad;
+  g.tilesw_log = ilog2_exact(g.tiles_w);
+  g.tpi_log = ilog2_exact(g.tiles_w * g.tiles_h);
+  if (g.tilesw_log < 0 || g.tpi_log < 0 || g.PP >= 65536 || g.patch_pix >= 65536) return false;
+  g.mPP = (uint32_t)(((1ull << 32) + g.PP - 1) / g.PP);
+  g.mPW = (uint32_t)(((1ull << 32) + g.PW - 1) / g.PW);
   return true;
 }
 
