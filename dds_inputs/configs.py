@@ -264,6 +264,15 @@ def tiny_cnn(K=2, W=2, B=4, hw=8, c=4, precision="f32", steps=8, momentum=0.9, b
                     momentum=momentum, steps=steps)
 
 
+def uneven_cnn(W=2, B=128, hw=16, precision="bf16", steps=2) -> Workload:
+    """3 -> 32 -> 128 -> 64 channels, stride 1, one module: layers whose input and output widths differ by
+    a factor of two to four, at a pixel count (W * B * hw * hw >= 65536) that selects the large pixel tiles."""
+    ops = [_conv(3, 32), _relu(), _conv(32, 128), _relu(), _conv(128, 64), _relu(), {"op": "gap"},
+           _linear(64, 10), {"op": "softmax_ce"}]
+    return Workload(name="uneven_cnn", ops=ops, bounds=[0, len(ops)], K=1, W=W, B=B, in_shape=(3, hw, hw),
+                    classes=10, precision=precision, lr=0.05, momentum=0.0, steps=steps)
+
+
 def tiny_mlp(K=3, W=2, B=4, feat=12, hidden=8, precision="f32", steps=10) -> Workload:
     """K linear layers (ReLU between), one per module: the cfg0 structure at toy size."""
     ops, bounds = [], [0]

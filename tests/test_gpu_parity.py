@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 from dds_inputs import workload
-from dds_inputs.configs import odd_resnet, tiny_cnn, tiny_mlp, tiny_resnet
+from dds_inputs.configs import odd_resnet, tiny_cnn, tiny_mlp, tiny_resnet, uneven_cnn
 from parity import bf16_round, check_parity, flat_init, run_hip, run_oracle, thresholds
 
 pytestmark = pytest.mark.gpu
@@ -102,6 +102,13 @@ def test_sixteen_channel_layers_bf16():
     _compare(tiny_resnet(K=1, W=1, B=1, hw=16, c=16, precision="bf16"), seed=9, T=3, every_step=True)
     # 32 x 32 images (two 16-pixel runs per image row); the second and third block are 32 channels wide at 16 x 16
     _compare(tiny_resnet(K=3, W=2, B=3, hw=32, c=16, precision="bf16"), seed=10, T=8)
+
+
+def test_uneven_channel_widths_large_pixel_tiles_bf16():
+    # 32 -> 128 and 128 -> 64 channels at 65536 pixels: the 256-pixel tiles with one 64-byte channel chunk and
+    # 128 output columns (forward of the first), and with several chunks and 64 output columns (its dgrad, and
+    # the forward of the second), which the ResNet shapes never select
+    _compare(uneven_cnn(), seed=11, T=2)
 
 
 def test_odd_shapes_fp32_and_bf16():
