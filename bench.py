@@ -47,6 +47,44 @@ def read_traffic(workload_name, key):
     return None
 
 
+def algorithmic_bytes_per_step(wl, residual_passes=True):
+    """HBM bytes one step has to move if every tensor crossed HBM exactly once per pass: for each
+    convolution / linear layer 3 x (input + output) activations (forward, dgrad, wgrad) in the compute
+    precision, plus the fp32 master weights read and written by the update and the compute-precision
+    copy read by the three passes; a residual block adds its projection (a convolution) or two more passes
+    over the block's tensor. Pools, rings and sign planes are left out: a lower bound."""
+    es = 2 if wl.precision == "bf16" else 4
+    n = wl.W * wl.B
+    c, h, w = wl.in_shape
+    blk = (c, h, w)
+    total = 0
+    for op in wl.ops:
+        k = op["op"]
+        if k == "conv":
+            ho = (h + 2 * op["pad"] - op["k"]) // op["stride"] + 1
+            wo = (w + 2 * op["pad"] - op["k"]) // op["stride"] + 1
+            nw = op["cout"] * op["cin"] * op["k"] * op["k"]
+            total += 3 * n * (op["cin"] * h * w + op["cout"] * ho * wo) * es + nw * (8 + 3 * es)
+            c, h, w = op["cout"], ho, wo
+        elif k == "linear":
+            total += 3 * n * (op["cin"] + op["cout"]) * es + op["cin"] * op["cout"] * (8 + 3 * es)
+            c, h, w = op["cout"], 1, 1
+        elif k == "res_begin":
+            blk = (c, h, w)
+        elif k == "res_add":
+            sc = op.get("shortcut")
+            if sc:  # projection: a convolution from the block input to the block output
+                nw = sc["cout"] * sc["cin"] * sc["k"] * sc["k"]
+                total += 3 * n * (sc["cin"] * blk[1] * blk[2] + c * h * w) * es + nw * (8 + 3 * es)
+            elif residual_passes:  # identity: the block input is read once more going forward, its gradient once going back
+                total += 2 * n * c * h * w * es
+        elif k == "maxpool2":
+            h, w = h // 2, w // 2
+        elif k == "gap":
+            h, w = 1, 1
+    return total
+
+
 def cpu_baseline(wl, seconds_budget=20.0):
     """The oracle as it stands on a bounded sample: same K / W / delays / layers with a
     reduced per-replica batch, timed over steady-state iterations."""
@@ -242,7 +280,12 @@ def main():
                      "all_gemm_launches": {"TFLOP/s": all_fl / max(all_ms, 1e-9) / 1e9, "avg_us": 1e3 * all_ms / max(all_n, 1),
                                            "launches_per_step": all_n / nprof},
                      "whole_step_TFLOP/s": flops / (ms_per_step * 1e-3) / 1e12,
-                     "whole_step_frac": flops / (ms_per_step * 1e-3) / 1e12 / peak},
+                     "whole_step_frac": flops / (ms_per_step * 1e-3) / 1e12 / peak,
+                     "whole_step_hbm": {"note": "lower bound on HBM bytes per step (see algorithmic_bytes_per_step) over the measured step time",
+                                        "algorithmic_GiB_per_step": algorithmic_bytes_per_step(wl) / 2 ** 30,
+                                        "conv_and_linear_passes_only_GiB": algorithmic_bytes_per_step(wl, False) / 2 ** 30,
+                                        "TB/s": algorithmic_bytes_per_step(wl) / (ms_per_step * 1e-3) / 1e12,
+                                        "frac_of_8_TB/s": algorithmic_bytes_per_step(wl) / (ms_per_step * 1e-3) / 8e12}},
     }
     tr.close()
     if not args.no_cpu_baseline:
